@@ -1,0 +1,90 @@
+"""Pins of the strategy-search oracle against hand-worked rankings (Algorithm 1) and the
+layer counts the paper's main table prints (32->28/24/20, 40->35/30/25, 48->42/36/30)."""
+import numpy as np
+import pytest
+
+from oracle import share_map as osm
+from paper_2410_18517_amd import inputs
+
+
+def _sym(L, entries, fill=0.0):
+    D = np.full((L, L), fill)
+    np.fill_diagonal(D, 0.0)
+    for (i, j), v in entries.items():
+        D[i, j] = D[j, i] = v
+    return D
+
+
+def test_hand_worked_four_layers():
+    # ranking, largest first: (1,3)=9, (0,3)=8, (0,2)=7, (1,2)=6, (2,3)=5, (0,1)=1
+    D = _sym(4, {(1, 3): 9, (0, 3): 8, (0, 2): 7, (1, 2): 6, (2, 3): 5, (0, 1): 1})
+    st, share, slot, n_slots, n = osm.build_share_map(D, 4, 1)
+    assert (st, share, slot, n_slots, n) == (0, [0, 1, 2, 1], [0, 1, 2, 1], 3, 1)
+    # C = 2: (0,3) is passed over (3 already receives), (0,2) accepted
+    st, share, slot, n_slots, n = osm.build_share_map(D, 4, 2)
+    assert (st, share, slot, n_slots, n) == (0, [0, 1, 0, 1], [0, 1, 0, 1], 2, 2)
+    # C = 3 cannot be reached at depth one: 0 and 1 donate, so (0,1) is passed over
+    st, share, _, n_slots, n = osm.build_share_map(D, 4, 3)
+    assert st == osm.TARGET_UNREACHED and n == 2 and share == [0, 1, 0, 1] and n_slots == 2
+
+
+def test_ascending_variant_takes_smallest_first():
+    D = _sym(4, {(1, 3): 9, (0, 3): 8, (0, 2): 7, (1, 2): 6, (2, 3): 5, (0, 1): 1})
+    _, share, _, _, _ = osm.build_share_map(D, 4, 1, ascending=True)
+    assert share == [0, 0, 2, 3]
+
+
+def test_donor_is_nearer_the_input_and_depth_one():
+    rng = np.random.default_rng(3)
+    for L, C in [(32, 4), (32, 8), (32, 12), (40, 5), (40, 10), (40, 15), (48, 6), (48, 12), (48, 18)]:
+        A = rng.random((L, L)); D = A + A.T; np.fill_diagonal(D, 0)
+        st, share, slot, n_slots, n = osm.build_share_map(D, L, C)
+        assert st == 0 and n == C and n_slots == L - C          # the table's "Layer" column
+        for l in range(L):
+            assert share[l] <= l and share[share[l]] == share[l]
+            assert slot[l] == slot[share[l]]
+        own = [l for l in range(L) if share[l] == l]
+        assert [slot[l] for l in own] == list(range(L - C))
+        # the first accepted pair is the arg-max of D
+        i, j = np.unravel_index(np.argmax(np.triu(D, 1)), D.shape)
+        assert share[j] == i
+
+
+def test_accept_predicate_controls_the_walk():
+    D = _sym(4, {(1, 3): 9, (0, 3): 8, (0, 2): 7, (1, 2): 6, (2, 3): 5, (0, 1): 1})
+    seen = []
+    st, share, _, _, n = osm.build_share_map(D, 4, 2, accept=lambda m: seen.append(list(m)) or False)
+    assert st == osm.TARGET_UNREACHED and n == 0 and share == [0, 1, 2, 3]
+    assert seen[0] == [0, 1, 2, 1] and len(seen) == 6        # every pair was tried, in rank order
+    # reject the first candidate only: (1,3) discarded, (0,3) then taken, then (0,2)
+    calls = []
+    def second_on(m):
+        calls.append(list(m))
+        return len(calls) > 1
+    st, share, _, _, n = osm.build_share_map(D, 4, 2, accept=second_on)
+    assert st == 0 and share == [0, 1, 0, 0]
+    assert calls == [[0, 1, 2, 1], [0, 1, 2, 0], [0, 1, 0, 0]]
+
+
+def test_ties_keep_pair_order_and_nan_rejected():
+    D = _sym(3, {(0, 1): 1, (0, 2): 1, (1, 2): 1})
+    assert osm.build_share_map(D, 3, 1)[1] == [0, 0, 2]
+    D[0, 1] = float("nan")
+    with pytest.raises(ValueError):
+        osm.build_share_map(D, 3, 1)
+
+
+def test_tiny_config_map_from_a_matrix_peaking_at_1_3():
+    D = _sym(4, {(1, 3): 5.0}, fill=1.0)
+    _, share, slot, n_slots, _ = osm.build_share_map(D, 4, 1)
+    want = inputs.make_share_map(4, 1, fixed=((3, 1),))
+    assert share == want.tolist() and n_slots == 3
+    assert slot == inputs.slots_of(want)[0].tolist()
+
+
+def test_seeded_maps_are_valid_depth_one():
+    for name, w in inputs.WORKLOADS.items():
+        m = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)
+        assert int((m != np.arange(w.L)).sum()) == w.n_shared
+        assert all(m[l] <= l and m[m[l]] == m[l] for l in range(w.L))
+        assert inputs.slots_of(m)[1] == w.L - w.n_shared
