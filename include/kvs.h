@@ -1,0 +1,199 @@
+/*
+ * kvs.h -- C ABI of libkvs: decode attention over a layer-shared KV cache on MI355X (gfx950).
+ *
+ * Method (KVSharer, arXiv 2410.18517): a sharing strategy names, for some layers, a donor
+ * layer nearer the input whose KV cache the layer reads instead of computing and storing
+ * its own (Sec. 3.2 and the prefill/generation figure); everything after the substitution
+ * is the host model's ordinary attention.  The strategy is found by ranking all layer
+ * pairs by the Euclidean distance between their calibration-averaged KV caches, most
+ * dissimilar first, and walking the ranking (Sec. 3.1.2, Algorithm 1).
+ *
+ * Conventions
+ *   - Every function returns a status: KVS_OK / KVS_NOOP are not errors; negatives are.
+ *     kvs_last_error() returns a thread-local description of the last failure.
+ *   - The caller owns all memory.  Pointers marked "device" are GPU allocations made by the
+ *     caller; "host" pointers are ordinary memory.  The library never allocates or frees
+ *     device memory and never synchronises: every kernel is enqueued on the hipStream_t the
+ *     caller passes as `void* stream` (NULL = the default stream).
+ *   - Every argument check that does not need the GPU runs before the first HIP call.
+ *   - share_map[l] is the layer whose cache layer l reads (l itself if l keeps its own);
+ *     valid maps have share_map[l] <= l and share_map[share_map[l]] == share_map[l].
+ *     slot_of_layer[l] is the KV-store slot of that cache; layers that keep their own
+ *     cache own slots 0..n_slots-1 in increasing layer order.
+ *
+ * KV store layout (device, one allocation of kvs_store_bytes()):
+ *     pool[slot][block][kv_head][K=0|V=1][page]     page = 16 tokens x head_dim elements
+ *   A page is contiguous (4 KiB for bf16, head_dim 128).  Token j of sequence b lives in
+ *   row j % 16 of block block_table[b][j / 16]; with block_table == NULL the store is
+ *   contiguous per sequence: that block is b * max_blocks_per_seq + j / 16.  One block table
+ *   serves all slots.  Element order inside a page:
+ *     KVS_F32 : [token][channel].
+ *     KVS_BF16: operand order of the matrix-core tiles that consume it, so a wavefront
+ *               reads 1 KiB contiguous per load and feeds it to MFMA untransposed:
+ *       K page: element (token t, channel c) at (((c/32)*4 + (c%32)/8)*16 + t)*8 + c%8
+ *       V page: element (t, c) at ((((c/32)*4 + t/4)*16 + c%16)*2 + (c/16)%2)*4 + t%4
+ *   Only kvs_append_kv writes pages and only the attention kernels / kvs_gather_kv read
+ *   them, so callers never depend on the in-page order.
+ */
+#ifndef KVS_H
+#define KVS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVS_OK                     0
+#define KVS_NOOP                   1   /* nothing to do (e.g. append on a layer that reads a donor) */
+#define KVS_ERR_INVALID_ARG       -1
+#define KVS_ERR_BAD_MAP           -2
+#define KVS_ERR_CAPACITY          -3
+#define KVS_ERR_TARGET_UNREACHED  -4
+#define KVS_ERR_UNSUPPORTED       -5
+#define KVS_ERR_HIP               -6
+
+#define KVS_F32   0
+#define KVS_BF16  1
+
+#define KVS_BLOCK_TOKENS 16
+
+const char* kvs_last_error(void);
+
+/* ---------------------------------------------------------------- strategy (host only) */
+
+/* Similarity test of Algorithm 1 ("Avg_Cos_Sim(...) > T"), supplied by the caller because
+ * it needs the model: return 1 to keep the candidate strategy, 0 to discard the pair. */
+typedef int (*kvs_accept_fn)(const int32_t* candidate_share_map, int L, void* user);
+
+/*
+ * Structural part of Algorithm 1 (ranking + greedy walk).  Pairs (i < j) are ranked by
+ * dist[i*L + j], largest first (order = 0, the paper's choice) or smallest first (order = 1,
+ * the "share similar layers" ablation of Sec. 5.1); ties keep (i, j) lexicographic order.
+ * In a pair the layer nearer the output (j) receives the cache of the layer nearer the input
+ * (i).  Strategies stay depth one: a pair is passed over -- no accept call, not counted --
+ * when j already receives or donates a cache or i already receives one.  The walk stops
+ * when target_shared layers receive a cache.
+ *   dist            host, L*L row-major, only the upper triangle is read; NaN -> INVALID_ARG
+ *   accept          NULL accepts every candidate
+ *   share_map, slot_of_layer   host, out[L];  n_slots, n_shared   host, out
+ * Returns KVS_OK, or KVS_ERR_TARGET_UNREACHED with the partial strategy in the outputs
+ * when the ranking is exhausted first (the paper's "return None").
+ */
+int kvs_build_share_map(const float* dist, int L, int target_shared, int order,
+                        kvs_accept_fn accept, void* user,
+                        int32_t* share_map, int32_t* slot_of_layer,
+                        int32_t* n_slots, int32_t* n_shared);
+
+/* KVS_OK iff the host array is a depth-one map with donor <= layer; else KVS_ERR_BAD_MAP. */
+int kvs_validate_share_map(const int32_t* share_map, int L);
+
+/* Slot numbering of a valid map (host in, host out[L]); *n_slots = layers keeping a cache. */
+int kvs_slots_from_share_map(const int32_t* share_map, int L, int32_t* slot_of_layer,
+                             int32_t* n_slots);
+
+/* ---------------------------------------------------------------- KV store */
+
+typedef struct kvs_desc {
+    int32_t L;                   /* layers of the model */
+    int32_t n_slots;             /* layer caches actually held: L - (shared layers) */
+    int32_t Hq, Hkv, head_dim;   /* Hq % Hkv == 0; query head h reads kv head h / (Hq/Hkv) */
+    int32_t dtype;               /* KVS_F32 or KVS_BF16: element type of the store and of q, k_new, v_new */
+    int32_t block_tokens;        /* must be KVS_BLOCK_TOKENS */
+    int32_t num_blocks;          /* blocks per slot */
+    int32_t max_blocks_per_seq;  /* columns of the block table; capacity = 16 * this */
+} kvs_desc;
+
+typedef struct kvs_store {
+    kvs_desc desc;
+    void* pool;                       /* device, kvs_store_bytes(&desc) bytes */
+    const int32_t* share_map;         /* device [L] */
+    const int32_t* slot_of_layer;     /* device [L] */
+    const int32_t* block_table;       /* device [B][max_blocks_per_seq], or NULL = contiguous */
+    const int32_t* host_share_map;    /* host [L]: same values; used for checks and KVS_NOOP only */
+    const int32_t* host_slot_of_layer;/* host [L] */
+} kvs_store;
+
+/* Bytes of the pool; 0 (with kvs_last_error set) if the descriptor is invalid/unsupported.
+ * Supported: KVS_BF16 with head_dim 128 or 64 and Hq/Hkv <= 16; KVS_F32 with head_dim a
+ * multiple of 64 up to 256. */
+size_t kvs_store_bytes(const kvs_desc* desc);
+
+/* Bytes of scratch the attention calls need for B sequences of up to max_q_rows query rows
+ * each (1 for decode).  The scratch holds split-context partial results and per-(sequence,
+ * kv head) arrival counters; the caller zero-fills it once after allocating it, and every
+ * call leaves the counters zero again.  Calls sharing one workspace must not overlap. */
+size_t kvs_workspace_bytes(const kvs_desc* desc, int B, int max_q_rows);
+
+/*
+ * Store this step's keys/values of `layer` (Sec. 3.2: only layers that keep their own cache
+ * compute and store KV).  k_new, v_new: device [B][T_new][Hkv][head_dim] of desc.dtype,
+ * copied bit for bit.  Row i of sequence b goes to token position start_pos[b] + i
+ * (start_pos: device [B]); positions >= capacity are dropped.
+ * Returns KVS_NOOP without touching the GPU when the layer reads a donor's cache.
+ */
+int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const void* v_new,
+                  const int32_t* start_pos, int B, int T_new, void* stream);
+
+/*
+ * Read back T tokens starting at t0 of every sequence from the cache `layer` attends to
+ * (its donor's when it has one), in the order kvs_append_kv takes:
+ * k_out, v_out device [B][T][Hkv][head_dim].  Inverse of kvs_append_kv; for checks, cache
+ * migration and debugging.
+ */
+int kvs_gather_kv(const kvs_store* store, int layer, int t0, int T, int B,
+                  void* k_out, void* v_out, void* stream);
+
+/*
+ * One decode step of `layer` (Sec. 3.2): out[b][h][:] = softmax_j(q[b][h] . K[b][g][j] /
+ * sqrt(head_dim)) . V[b][g][j][:] over j < seq_lens[b], g = h / (Hq/Hkv), where K, V are
+ * the cache of slot_of_layer[share_map[layer]] -- resolved on the device.  seq_lens counts
+ * the token appended this step.  seq_lens[b] == 0 gives a zero row; values above the
+ * capacity are clamped to it.
+ *   q device [B][Hq][head_dim] of desc.dtype;  seq_lens device [B];  out device fp32
+ *   [B][Hq][head_dim];  workspace device, >= kvs_workspace_bytes(desc, B, 1).
+ */
+int kvs_decode_attention(const kvs_store* store, int layer, const void* q,
+                         const int32_t* seq_lens, int B, float* out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Causal attention of T_new new query rows per sequence (the prefill side of Sec. 3.2):
+ * row i of sequence b sits at position start_pos[b] + i and sees keys 0..start_pos[b] + i of
+ * the cache `layer` attends to, which must already hold them (append first; a recipient's
+ * donor, being nearer the input, has been appended earlier in the same pass).
+ *   q device [B][T_new][Hq][head_dim];  out device fp32 [B][T_new][Hq][head_dim];
+ *   workspace >= kvs_workspace_bytes(desc, B, T_new).
+ */
+int kvs_prefill_attention(const kvs_store* store, int layer, const void* q,
+                          const int32_t* start_pos, int B, int T_new, float* out,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* Context tokens handled by one workgroup of the split-context decode kernel; 0 restores the
+ * built-in choice.  Must be a multiple of 64.  Process-wide; for tuning and tests. */
+int kvs_set_split_tokens(int tokens);
+
+/* ---------------------------------------------------------------- calibration distance */
+
+/*
+ * Layer-dissimilarity matrix of the strategy search (Sec. 3.1.2, Algorithm 1 first step).
+ * kv_samples: device [S][L][2][N] of `dtype`: calibration sample, layer, keys(0)/values(1),
+ * flattened [Hkv][T][head_dim] index; all samples have the same length.  The keys and the
+ * values of a layer are averaged over the S samples, and
+ *   dK2[a][b] = || meanK_a - meanK_b ||^2,  dV2 likewise,  D[a][b] = sqrt(dK2 + dV2)
+ * i.e. the Euclidean distance between the flattened [mean K ; mean V] vectors.  Outputs are
+ * device fp32 [L][L], symmetric with a zero diagonal; dK2 and dV2 are returned so that other
+ * readings of "average the keys and values separately" can be formed by the caller.
+ * Supported: L <= 64.  workspace >= kvs_distance_workspace_bytes(L).
+ */
+int kvs_layer_distance(const void* kv_samples, int S, int L, size_t N, int dtype,
+                       float* dK2, float* dV2, float* D,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+size_t kvs_distance_workspace_bytes(int L);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVS_H */

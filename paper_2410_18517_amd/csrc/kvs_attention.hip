@@ -1,0 +1,511 @@
+// Attention over the slot-indexed, paged KV store (gfx950): append / gather, the fp32
+// reference-precision kernel, the bf16 split-context MFMA kernel and the split combine.
+//
+// The operation is the ordinary attention of the host model after the sharing strategy has
+// redirected a layer to its donor's cache (paper Sec. 3.2): the only method-specific step in
+// the kernels is the two-level lookup slot_of_layer[share_map[layer]], done on the device.
+#include <hip/hip_runtime.h>
+
+#include "kvs_internal.h"
+
+namespace kvs {
+namespace {
+
+constexpr int kPageTokens = 16;
+constexpr int kWaves = 4;              // wavefronts per workgroup of the bf16 kernel
+constexpr int kThreads = kWaves * 64;
+constexpr int kPrefetch = 3;           // pages each wavefront keeps in flight
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2;
+
+__device__ __forceinline__ int resolve_slot(const StoreView& st)
+{
+    // the strategy's substitution: a layer reads the cache of its donor (itself if none)
+    int donor = st.share_map[st.layer];
+    donor = donor < 0 ? 0 : (donor >= st.L ? st.L - 1 : donor);
+    const int slot = st.slot_of_layer[donor];
+    return slot < 0 ? 0 : (slot >= st.n_slots ? st.n_slots - 1 : slot);
+}
+
+// Physical block of logical page `page` of sequence b.
+__device__ __forceinline__ int block_of(const StoreView& st, int b, int page)
+{
+    const int idx = b * st.max_blocks_per_seq + page;
+    return st.block_table ? st.block_table[idx] : idx;
+}
+
+// Same, forced into the pool: a corrupt table entry must not turn into a wild read.
+__device__ __forceinline__ int safe_block_of(const StoreView& st, int b, int page)
+{
+    const int blk = block_of(st, b, page);
+    return blk < 0 ? 0 : (blk >= st.num_blocks ? st.num_blocks - 1 : blk);
+}
+
+// Element offset of the K page of (slot, block, kv head); the V page follows it.
+__device__ __forceinline__ size_t page_offset(const StoreView& st, int slot, int blk, int g)
+{
+    return (((size_t)slot * st.num_blocks + blk) * st.Hkv + g) * 2 * (size_t)(kPageTokens * st.head_dim);
+}
+
+// In-page element index of (token t, channel c) for the bf16 store.
+__device__ __forceinline__ int k_index_bf16(int t, int c)
+{
+    return (((c >> 5) * 4 + ((c & 31) >> 3)) * 16 + t) * 8 + (c & 7);
+}
+__device__ __forceinline__ int v_index_bf16(int t, int c)
+{
+    return ((((c >> 5) * 4 + (t >> 2)) * 16 + (c & 15)) * 2 + ((c >> 4) & 1)) * 4 + (t & 3);
+}
+
+// ------------------------------------------------------------------ append / gather
+// One thread moves 8 consecutive channels (bf16) or 4 (fp32) of one (sequence, row, kv head).
+template <bool kToStore>
+__global__ void copy_rows_kernel(CopyArgs a)
+{
+    const StoreView& st = a.st;
+    const int D = st.head_dim;
+    const int per = st.dtype == 1 ? 8 : 4;
+    const int chunks = D / per;
+    const long total = (long)a.B * a.T * st.Hkv * chunks;
+    const long tid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid >= total) return;
+    const int ch = (int)(tid % chunks);
+    const int g = (int)((tid / chunks) % st.Hkv);
+    const int i = (int)((tid / ((long)chunks * st.Hkv)) % a.T);
+    const int b = (int)(tid / ((long)chunks * st.Hkv * a.T));
+    const long pos = (long)(a.start_pos ? a.start_pos[b] : a.t0) + i;
+    if (pos < 0 || pos >= (long)st.max_blocks_per_seq * kPageTokens) return;
+    const int slot = resolve_slot(st);
+    const int blk = block_of(st, b, (int)(pos / kPageTokens));
+    if (blk < 0 || blk >= st.num_blocks) return;
+    const int t = (int)(pos % kPageTokens);
+    const size_t page = page_offset(st, slot, blk, g);
+    const size_t row = (((size_t)b * a.T + i) * st.Hkv + g) * D + (size_t)ch * per;
+    if (st.dtype == 1) {
+        unsigned short* pool = static_cast<unsigned short*>(st.pool);
+        unsigned short* kp = pool + page;
+        unsigned short* vp = kp + kPageTokens * D;
+        unsigned short* kr = static_cast<unsigned short*>(a.k) + row;
+        unsigned short* vr = static_cast<unsigned short*>(a.v) + row;
+        const int c0 = ch * 8;
+        if (kToStore) {
+            *reinterpret_cast<uint4*>(kp + k_index_bf16(t, c0)) = *reinterpret_cast<const uint4*>(kr);
+            const uint4 vv = *reinterpret_cast<const uint4*>(vr);
+            const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                vp[v_index_bf16(t, c0 + e)] = (unsigned short)(w[e >> 1] >> ((e & 1) * 16));
+        } else {
+            *reinterpret_cast<uint4*>(kr) = *reinterpret_cast<const uint4*>(kp + k_index_bf16(t, c0));
+            unsigned w[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                w[e >> 1] |= (unsigned)vp[v_index_bf16(t, c0 + e)] << ((e & 1) * 16);
+            *reinterpret_cast<uint4*>(vr) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    } else {
+        float* pool = static_cast<float*>(st.pool);
+        float* kp = pool + page + (size_t)t * D + ch * 4;
+        float* vp = kp + kPageTokens * D;
+        float* kr = static_cast<float*>(a.k) + row;
+        float* vr = static_cast<float*>(a.v) + row;
+        if (kToStore) {
+            *reinterpret_cast<float4*>(kp) = *reinterpret_cast<const float4*>(kr);
+            *reinterpret_cast<float4*>(vp) = *reinterpret_cast<const float4*>(vr);
+        } else {
+            *reinterpret_cast<float4*>(kr) = *reinterpret_cast<const float4*>(kp);
+            *reinterpret_cast<float4*>(vr) = *reinterpret_cast<const float4*>(vp);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ fp32 store
+// One wavefront per (sequence, query row, query head); the whole context in one pass.
+// Lanes own tokens for the scores and channels for the weighted sum.
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+__global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a)
+{
+    const StoreView& st = a.st;
+    const int D = st.head_dim;                       // 64, 128, 192 or 256
+    const int h = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x;
+    const int group = st.Hq / st.Hkv;
+    const int g = h / group;
+    const long cap = (long)st.max_blocks_per_seq * kPageTokens;
+    long n = (long)a.lens[b] + a.lens_bias + r;
+    n = n < 0 ? 0 : (n > cap ? cap : n);
+    const size_t row = (((size_t)b * a.T_new + r) * st.Hq + h) * D;
+    __shared__ float qs[256];
+    const float* q = static_cast<const float*>(a.q) + row;
+    for (int c = lane; c < D; c += 64) qs[c] = q[c];
+    __syncthreads();
+    const int slot = resolve_slot(st);
+    const float* pool = static_cast<const float*>(st.pool);
+    const float scale_log2 = 1.44269504088896340736f / sqrtf((float)D);
+    float m = -INFINITY, l = 0.f;
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+    for (long j0 = 0; j0 < n; j0 += 64) {
+        const long j = j0 + lane;
+        float z = -INFINITY;
+        if (j < n) {
+            const int blk = safe_block_of(st, b, (int)(j / kPageTokens));
+            const float* kp = pool + page_offset(st, slot, blk, g) + (size_t)(j % kPageTokens) * D;
+            float dot = 0.f;
+            for (int c = 0; c < D; ++c) dot = fmaf(qs[c], kp[c], dot);
+            z = dot * scale_log2;
+        }
+        const float m_new = fmaxf(m, wave_max(z));     // finite: the tile holds token j0 < n
+        const float alpha = exp2f(m - m_new);
+        const float p = exp2f(z - m_new);
+        l = l * alpha + wave_sum(p);
+        m = m_new;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] *= alpha;
+        const int cnt = (int)((n - j0) < 64 ? (n - j0) : 64);
+        for (int t = 0; t < cnt; ++t) {
+            const float pt = __shfl(p, t);
+            const long jj = j0 + t;
+            const int blk = safe_block_of(st, b, (int)(jj / kPageTokens));
+            const float* vp = pool + page_offset(st, slot, blk, g) + (size_t)kPageTokens * D +
+                              (size_t)(jj % kPageTokens) * D;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (lane + 64 * e < D) o[e] = fmaf(pt, vp[lane + 64 * e], o[e]);
+        }
+    }
+    const float inv = n > 0 ? 1.f / l : 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (lane + 64 * e < D) a.out[row + lane + 64 * e] = o[e] * inv;
+}
+
+// ------------------------------------------------------------------ bf16 store, MFMA
+//
+// Work split: grid = (n_splits * n_col_groups, Hkv, B).  A workgroup owns one kv head of one
+// sequence, NT tiles of 16 query columns (a column is a (query row, head-in-group) pair; a
+// decode step has one row, so one tile holds the whole GQA group) and a contiguous range of
+// pages.  Its four wavefronts take pages round-robin, each streaming its pages from HBM
+// straight into MFMA operand registers (the store's in-page order is the operand order) with
+// kPrefetch pages in flight, and keeps a private online-softmax state.  The states merge
+// through LDS at the end; with more than one split the merged, unnormalised state goes to
+// the partials buffer for the combine kernel.
+//
+// MFMA roles.  Scores: S[token][column] = K_page(16 x D) . Q^T(D x 16) with
+// v_mfma_f32_16x16x32_bf16; lane l holds the scores of column l%16 for tokens 4*(l/16)..+3,
+// which is exactly the B-operand layout of v_mfma_f32_16x16x16_bf16, so the probabilities feed
+// O^T[channel][column] += V^T(16 x 16 tokens) . P^T(16 tokens x 16 columns) without leaving
+// their registers.
+template <int D>
+struct PageRegs {
+    uint4 k[D / 32];
+    uint4 v[D / 32];
+};
+
+template <int D>
+__device__ __forceinline__ void load_page(PageRegs<D>& r, const unsigned short* pool, size_t page_off, int lane)
+{
+    const uint4* kp = reinterpret_cast<const uint4*>(pool + page_off) + lane;
+    const uint4* vp = kp + (kPageTokens * D * 2) / 16;
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) r.k[s] = kp[s * 64];
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) r.v[s] = vp[s * 64];
+}
+
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
+{
+    floatx2 f = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
+}
+
+template <int D, int NT>
+__global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
+{
+    constexpr int KS = D / 32;   // k-steps of the score MFMA = 1-KiB chunks per page
+    constexpr int DT = D / 16;   // 16-channel tiles of the output
+    const StoreView& st = a.st;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int quad = lane >> 4, col = lane & 15;
+    const int split = blockIdx.x % a.n_splits;
+    const int cgrp = blockIdx.x / a.n_splits;
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int group = st.Hq / st.Hkv;
+    const int ncols = a.T_new * group;
+    const int cap = st.max_blocks_per_seq * kPageTokens;
+
+    // keys visible to query row 0; row r sees n0 + r
+    int n0 = a.lens[b] + a.lens_bias;
+    n0 = n0 < 0 ? 0 : n0;
+    if (n0 > cap - (a.T_new - 1)) n0 = cap - (a.T_new - 1);
+
+    // columns of this lane, one per tile
+    int n_col[NT];
+    size_t q_off[NT];
+    bool col_ok[NT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        const int cidx = (cgrp * NT + ct) * 16 + col;
+        col_ok[ct] = cidx < ncols;
+        const int r = col_ok[ct] ? cidx / group : 0;
+        const int hc = col_ok[ct] ? cidx % group : 0;
+        n_col[ct] = n0 + r;
+        q_off[ct] = (((size_t)b * a.T_new + r) * st.Hq + g * group + hc) * D;
+    }
+    // rows covered by the workgroup bound the pages it needs
+    const int c_lo = cgrp * NT * 16;
+    int c_hi = c_lo + NT * 16 - 1;
+    if (c_hi > ncols - 1) c_hi = ncols - 1;
+    const int n_min = n0 + c_lo / group;          // fewest keys any of its rows sees
+    const int n_max = n0 + c_hi / group;          // most keys, = tokens certainly stored
+    const int pages_total = (n_max + kPageTokens - 1) / kPageTokens;
+    const int page_lo = split * a.pages_per_split;
+    int page_hi = page_lo + a.pages_per_split;
+    if (page_hi > pages_total) page_hi = pages_total;
+
+    // query fragments: B operand of the score MFMA
+    bf16x8 qf[NT][KS];
+    const unsigned short* qbase = static_cast<const unsigned short*>(a.q);
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            uint4 w = make_uint4(0, 0, 0, 0);
+            if (col_ok[ct]) w = *reinterpret_cast<const uint4*>(qbase + q_off[ct] + s * 32 + quad * 8);
+            qf[ct][s] = __builtin_bit_cast(bf16x8, w);
+        }
+
+    const float scale_log2 = 1.44269504088896340736f * (D == 128 ? 0.08838834764831845f : 0.125f);
+    float m[NT], l[NT];
+    floatx4 o[NT][DT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        m[ct] = -INFINITY;
+        l[ct] = 0.f;
+#pragma unroll
+        for (int c = 0; c < DT; ++c) o[ct][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int slot = resolve_slot(st);
+    const unsigned short* pool = static_cast<const unsigned short*>(st.pool);
+    const int my_first = page_lo + wave;
+    const int my_pages = my_first < page_hi ? (page_hi - my_first + kWaves - 1) / kWaves : 0;
+
+    PageRegs<D> buf[kPrefetch];
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j)
+        if (j < my_pages)
+            load_page<D>(buf[j], pool, page_offset(st, slot, safe_block_of(st, b, my_first + j * kWaves), g), lane);
+
+    for (int k0 = 0; k0 < my_pages; k0 += kPrefetch) {
+#pragma unroll
+        for (int j = 0; j < kPrefetch; ++j) {
+            const int k = k0 + j;
+            if (k >= my_pages) break;
+            const int page = my_first + k * kWaves;
+            const int tok0 = page * kPageTokens;
+            PageRegs<D>& cur = buf[j];
+
+            if (tok0 + kPageTokens > n_max) {
+                // tokens past the stored length hold whatever the allocation held: clear their
+                // values so a zero probability cannot meet a NaN
+                const int t = tok0 + quad * 4;
+                const unsigned m01 = (t + 0 < n_max ? 0x0000ffffu : 0u) | (t + 1 < n_max ? 0xffff0000u : 0u);
+                const unsigned m23 = (t + 2 < n_max ? 0x0000ffffu : 0u) | (t + 3 < n_max ? 0xffff0000u : 0u);
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    cur.v[s].x &= m01; cur.v[s].y &= m23; cur.v[s].z &= m01; cur.v[s].w &= m23;
+                }
+            }
+            const bool need_mask = tok0 + kPageTokens > n_min;
+
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                floatx4 sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[s]),
+                                                                 qf[ct][s], sc, 0, 0, 0);
+                float z[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) z[i] = sc[i] * scale_log2;
+                if (need_mask) {
+                    const int t = tok0 + quad * 4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) z[i] = (t + i < n_col[ct]) ? z[i] : -INFINITY;
+                }
+                float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m[ct], mx);
+                const float m_use = m_new == -INFINITY ? 0.f : m_new;   // column sees nothing yet
+                const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_use);
+                float p[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_use);
+                l[ct] = l[ct] * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+                if (!__all(m_new == m[ct])) {
+#pragma unroll
+                    for (int c = 0; c < DT; ++c) o[ct][c] *= alpha;
+                }
+                m[ct] = m_new;
+                const uint2 pw = make_uint2(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]));
+                const shortx4 pf = __builtin_bit_cast(shortx4, pw);
+#pragma unroll
+                for (int c = 0; c < DT; ++c) {
+                    const uint4 vv = cur.v[c >> 1];
+                    const uint2 half = (c & 1) ? make_uint2(vv.z, vv.w) : make_uint2(vv.x, vv.y);
+                    o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, half), pf,
+                                                                         o[ct][c], 0, 0, 0);
+                }
+            }
+            if (k + kPrefetch < my_pages)
+                load_page<D>(buf[j], pool,
+                             page_offset(st, slot, safe_block_of(st, b, page + kPrefetch * kWaves), g), lane);
+        }
+    }
+
+    // merge the four wavefront states, one column tile at a time
+    __shared__ float lds_o[kWaves][16][D + 4];
+    __shared__ float lds_m[kWaves][16];
+    __shared__ float lds_l[kWaves][16];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        float lsum = l[ct];
+        lsum += __shfl_xor(lsum, 16);
+        lsum += __shfl_xor(lsum, 32);
+        if (ct > 0) __syncthreads();
+        if (quad == 0) {
+            lds_m[wave][col] = m[ct];
+            lds_l[wave][col] = lsum;
+        }
+#pragma unroll
+        for (int c = 0; c < DT; ++c)
+            *reinterpret_cast<floatx4*>(&lds_o[wave][col][c * 16 + quad * 4]) = o[ct][c];
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < 16 * (D / 4); idx += kThreads) {
+            const int cc = idx / (D / 4);
+            const int d4 = (idx % (D / 4)) * 4;
+            const int cidx = (cgrp * NT + ct) * 16 + cc;
+            if (cidx >= ncols) continue;
+            float mw[kWaves], M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) { mw[w] = lds_m[w][cc]; M = fmaxf(M, mw[w]); }
+            const float M_use = M == -INFINITY ? 0.f : M;
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+            float lt = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float wgt = __builtin_amdgcn_exp2f(mw[w] - M_use);
+                acc += wgt * *reinterpret_cast<const floatx4*>(&lds_o[w][cc][d4]);
+                lt += wgt * lds_l[w][cc];
+            }
+            const int r = cidx / group, hc = cidx % group;
+            const size_t row = ((size_t)b * a.T_new + r) * st.Hq + g * group + hc;
+            if (a.n_splits == 1) {
+                const float inv = lt > 0.f ? 1.f / lt : 0.f;
+                *reinterpret_cast<floatx4*>(a.out + row * D + d4) = acc * inv;
+            } else {
+                float* part = a.partials + (row * a.n_splits + split) * (size_t)(D + 2);
+                // (D + 2) floats per record keeps 8-byte alignment only: store as pairs
+                *reinterpret_cast<floatx2*>(part + d4) = floatx2{acc[0], acc[1]};
+                *reinterpret_cast<floatx2*>(part + d4 + 2) = floatx2{acc[2], acc[3]};
+                if (d4 == 0) *reinterpret_cast<floatx2*>(part + D) = floatx2{M, lt};
+            }
+        }
+    }
+}
+
+// Merge the per-split states of one output row: grid (Hq, T_new, B), D threads.
+template <int D>
+__global__ __launch_bounds__(D) void combine_kernel(AttnArgs a)
+{
+    const int h = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
+    const size_t row = ((size_t)b * a.T_new + r) * a.st.Hq + h;
+    const float* part = a.partials + row * a.n_splits * (size_t)(D + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, part[s * (D + 2) + D]);
+    const float M_use = M == -INFINITY ? 0.f : M;
+    float acc = 0.f, lt = 0.f;
+    for (int s = 0; s < a.n_splits; ++s) {
+        const float* ps = part + s * (D + 2);
+        const float wgt = __builtin_amdgcn_exp2f(ps[D] - M_use);
+        if (wgt > 0.f) {                      // empty splits carry m = -inf and are skipped
+            acc += wgt * ps[threadIdx.x];
+            lt += wgt * ps[D + 1];
+        }
+    }
+    a.out[row * D + threadIdx.x] = lt > 0.f ? acc / lt : 0.f;
+}
+
+template <int D>
+int launch_bf16(const AttnArgs& a, hipStream_t s)
+{
+    const int group = a.st.Hq / a.st.Hkv;
+    if (a.T_new == 1) {
+        dim3 grid(a.n_splits, a.st.Hkv, a.B);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, 1>), grid, dim3(kThreads), 0, s, a);
+    } else {
+        const int cgroups = (a.T_new * group + 63) / 64;
+        dim3 grid(a.n_splits * cgroups, a.st.Hkv, a.B);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, 4>), grid, dim3(kThreads), 0, s, a);
+    }
+    if (hipError_t e = hipGetLastError()) return (int)e;
+    if (a.n_splits > 1) {
+        dim3 grid(a.st.Hq, a.T_new, a.B);
+        hipLaunchKernelGGL((combine_kernel<D>), grid, dim3(D), 0, s, a);
+        if (hipError_t e = hipGetLastError()) return (int)e;
+    }
+    return 0;
+}
+
+}  // namespace
+
+int launch_append(const CopyArgs& a, void* stream)
+{
+    const int per = a.st.dtype == 1 ? 8 : 4;
+    const long total = (long)a.B * a.T * a.st.Hkv * (a.st.head_dim / per);
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(copy_rows_kernel<true>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    return (int)hipGetLastError();
+}
+
+int launch_gather(const CopyArgs& a, void* stream)
+{
+    const int per = a.st.dtype == 1 ? 8 : 4;
+    const long total = (long)a.B * a.T * a.st.Hkv * (a.st.head_dim / per);
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(copy_rows_kernel<false>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    return (int)hipGetLastError();
+}
+
+int launch_attention(const AttnArgs& a, void* stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (a.st.dtype == 0) {
+        dim3 grid(a.st.Hq, a.T_new, a.B);
+        hipLaunchKernelGGL(attn_f32_kernel, grid, dim3(64), 0, s, a);
+        return (int)hipGetLastError();
+    }
+    return a.st.head_dim == 128 ? launch_bf16<128>(a, s) : launch_bf16<64>(a, s);
+}
+
+const char* hip_error_string(int err) { return hipGetErrorString(static_cast<hipError_t>(err)); }
+
+}  // namespace kvs

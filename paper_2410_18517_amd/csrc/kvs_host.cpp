@@ -1,0 +1,374 @@
+// Host side of libkvs: argument checks, the strategy-search walk, launch geometry.
+// Everything that can be decided without the GPU is decided here, before any HIP call.
+#include "../../include/kvs.h"
+#include "kvs_internal.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <numeric>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+std::atomic<int> g_split_tokens{0};
+
+// Workgroups the decode grid should at least reach: 256 compute units, several resident
+// workgroups each, and enough left over that ragged batches even out.
+constexpr int kTargetWorkgroups = 2048;
+constexpr int kMinPagesPerSplit = 4;   // one page per wavefront of the workgroup
+
+int check_desc(const kvs_desc* d)
+{
+    if (!d) return fail(KVS_ERR_INVALID_ARG, "descriptor is NULL");
+    if (d->L <= 0 || d->n_slots <= 0 || d->n_slots > d->L)
+        return fail(KVS_ERR_INVALID_ARG, "need 0 < n_slots <= L (L=%d, n_slots=%d)", d->L, d->n_slots);
+    if (d->Hq <= 0 || d->Hkv <= 0 || d->Hq % d->Hkv != 0)
+        return fail(KVS_ERR_INVALID_ARG, "Hq=%d must be a positive multiple of Hkv=%d", d->Hq, d->Hkv);
+    if (d->block_tokens != KVS_BLOCK_TOKENS)
+        return fail(KVS_ERR_UNSUPPORTED, "block_tokens must be %d (got %d)", KVS_BLOCK_TOKENS, d->block_tokens);
+    if (d->num_blocks <= 0 || d->max_blocks_per_seq <= 0)
+        return fail(KVS_ERR_INVALID_ARG, "num_blocks and max_blocks_per_seq must be positive");
+    if (d->max_blocks_per_seq > (1 << 26))
+        return fail(KVS_ERR_CAPACITY, "max_blocks_per_seq too large");
+    if (d->dtype == KVS_BF16) {
+        if (d->head_dim != 128 && d->head_dim != 64)
+            return fail(KVS_ERR_UNSUPPORTED, "bf16 store supports head_dim 64 or 128 (got %d)", d->head_dim);
+        if (d->Hq / d->Hkv > 16)
+            return fail(KVS_ERR_UNSUPPORTED, "bf16 store supports at most 16 query heads per kv head");
+    } else if (d->dtype == KVS_F32) {
+        if (d->head_dim <= 0 || d->head_dim % 64 != 0 || d->head_dim > 256)
+            return fail(KVS_ERR_UNSUPPORTED, "fp32 store supports head_dim 64, 128, 192 or 256 (got %d)", d->head_dim);
+    } else {
+        return fail(KVS_ERR_UNSUPPORTED, "unknown dtype %d", d->dtype);
+    }
+    return KVS_OK;
+}
+
+size_t elem_bytes(int dtype) { return dtype == KVS_BF16 ? 2 : 4; }
+
+int check_map(const int32_t* m, int L)
+{
+    if (!m || L <= 0) return fail(KVS_ERR_INVALID_ARG, "share map is NULL or L <= 0");
+    for (int l = 0; l < L; ++l) {
+        if (m[l] < 0 || m[l] > l)
+            return fail(KVS_ERR_BAD_MAP, "share_map[%d]=%d: a donor must be the layer itself or one nearer the input", l, m[l]);
+        if (m[m[l]] != m[l])
+            return fail(KVS_ERR_BAD_MAP, "share_map[%d]=%d is itself a recipient (chains are not allowed)", l, m[l]);
+    }
+    return KVS_OK;
+}
+
+void number_slots(const int32_t* m, int L, int32_t* slot, int32_t* n_slots)
+{
+    int32_t next = 0;
+    for (int l = 0; l < L; ++l)
+        if (m[l] == l) slot[l] = next++;
+    for (int l = 0; l < L; ++l)
+        if (m[l] != l) slot[l] = slot[m[l]];
+    *n_slots = next;
+}
+
+int check_store(const kvs_store* s, int layer)
+{
+    if (!s) return fail(KVS_ERR_INVALID_ARG, "store is NULL");
+    if (int rc = check_desc(&s->desc)) return rc;
+    if (!s->pool || !s->share_map || !s->slot_of_layer || !s->host_share_map || !s->host_slot_of_layer)
+        return fail(KVS_ERR_INVALID_ARG, "store has a NULL pool, map or host mirror");
+    if (layer < 0 || layer >= s->desc.L)
+        return fail(KVS_ERR_INVALID_ARG, "layer %d out of range [0, %d)", layer, s->desc.L);
+    if (int rc = check_map(s->host_share_map, s->desc.L)) return rc;
+    for (int l = 0; l < s->desc.L; ++l) {
+        const int32_t sl = s->host_slot_of_layer[l];
+        if (sl < 0 || sl >= s->desc.n_slots)
+            return fail(KVS_ERR_BAD_MAP, "slot_of_layer[%d]=%d outside [0, %d)", l, sl, s->desc.n_slots);
+        if (sl != s->host_slot_of_layer[s->host_share_map[l]])
+            return fail(KVS_ERR_BAD_MAP, "layer %d and its donor %d disagree on the slot", l, s->host_share_map[l]);
+    }
+    return KVS_OK;
+}
+
+kvs::StoreView view_of(const kvs_store* s, int layer)
+{
+    kvs::StoreView v;
+    v.pool = s->pool;
+    v.share_map = s->share_map;
+    v.slot_of_layer = s->slot_of_layer;
+    v.block_table = s->block_table;
+    v.layer = layer;
+    v.L = s->desc.L;
+    v.n_slots = s->desc.n_slots;
+    v.Hq = s->desc.Hq;
+    v.Hkv = s->desc.Hkv;
+    v.head_dim = s->desc.head_dim;
+    v.dtype = s->desc.dtype;
+    v.num_blocks = s->desc.num_blocks;
+    v.max_blocks_per_seq = s->desc.max_blocks_per_seq;
+    return v;
+}
+
+// Query columns (row, head-in-group pairs) one workgroup of the bf16 kernel covers.
+int columns_per_workgroup(int T_new) { return T_new > 1 ? 64 : 16; }
+
+struct Split { int pages_per_split, n_splits, n_col_groups; };
+
+Split choose_split(const kvs_desc* d, int B, int T_new)
+{
+    Split s;
+    const int max_pages = d->max_blocks_per_seq;
+    if (d->dtype == KVS_F32) {           // the fp32 kernel walks the whole context in one wave
+        s.pages_per_split = max_pages;
+        s.n_splits = 1;
+        s.n_col_groups = 1;
+        return s;
+    }
+    const int group = d->Hq / d->Hkv;
+    s.n_col_groups = (T_new * group + columns_per_workgroup(T_new) - 1) / columns_per_workgroup(T_new);
+    int pps;
+    const int forced = g_split_tokens.load();
+    if (forced > 0) {
+        pps = forced / KVS_BLOCK_TOKENS;
+    } else {
+        const long items = (long)B * d->Hkv * s.n_col_groups;
+        long want = (kTargetWorkgroups + items - 1) / items;                 // splits wanted
+        want = std::max(1L, std::min<long>(want, max_pages / 16 > 0 ? max_pages / 16 : 1));
+        pps = (int)((max_pages + want - 1) / want);
+        pps = (pps + 3) / 4 * 4;
+    }
+    pps = std::max(kMinPagesPerSplit, std::min(pps, (max_pages + 3) / 4 * 4));
+    s.pages_per_split = pps;
+    s.n_splits = (max_pages + pps - 1) / pps;
+    return s;
+}
+
+size_t partial_floats(const kvs_desc* d, int B, int T_new, const Split& s)
+{
+    if (s.n_splits <= 1) return 0;
+    return (size_t)B * T_new * d->Hq * s.n_splits * (size_t)(d->head_dim + 2);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* kvs_last_error(void) { return g_last_error.c_str(); }
+
+int kvs_validate_share_map(const int32_t* share_map, int L) { return check_map(share_map, L); }
+
+int kvs_slots_from_share_map(const int32_t* share_map, int L, int32_t* slot_of_layer, int32_t* n_slots)
+{
+    if (!slot_of_layer || !n_slots) return fail(KVS_ERR_INVALID_ARG, "output pointer is NULL");
+    if (int rc = check_map(share_map, L)) return rc;
+    number_slots(share_map, L, slot_of_layer, n_slots);
+    return KVS_OK;
+}
+
+int kvs_build_share_map(const float* dist, int L, int target_shared, int order,
+                        kvs_accept_fn accept, void* user,
+                        int32_t* share_map, int32_t* slot_of_layer,
+                        int32_t* n_slots, int32_t* n_shared)
+{
+    if (!dist || !share_map || !slot_of_layer || !n_slots || !n_shared)
+        return fail(KVS_ERR_INVALID_ARG, "NULL argument");
+    if (L <= 0 || target_shared < 0 || target_shared >= L)
+        return fail(KVS_ERR_INVALID_ARG, "need L > 0 and 0 <= target_shared < L (L=%d, C=%d)", L, target_shared);
+    if (order != 0 && order != 1) return fail(KVS_ERR_INVALID_ARG, "order must be 0 or 1");
+
+    struct Pair { float d; int32_t i, j; };
+    std::vector<Pair> ranking;
+    ranking.reserve((size_t)L * (L - 1) / 2);
+    for (int i = 0; i < L; ++i)
+        for (int j = i + 1; j < L; ++j) {
+            const float v = dist[(size_t)i * L + j];
+            if (std::isnan(v)) return fail(KVS_ERR_INVALID_ARG, "dist[%d][%d] is NaN", i, j);
+            ranking.push_back({v, i, j});
+        }
+    // Pairs were generated in (i, j) order, so a stable sort keeps that order among ties.
+    if (order == 0)
+        std::stable_sort(ranking.begin(), ranking.end(), [](const Pair& a, const Pair& b) { return a.d > b.d; });
+    else
+        std::stable_sort(ranking.begin(), ranking.end(), [](const Pair& a, const Pair& b) { return a.d < b.d; });
+
+    std::vector<int32_t> map(L), candidate(L);
+    std::iota(map.begin(), map.end(), 0);
+    std::vector<char> donates(L, 0);
+    int shared = 0;
+    for (const Pair& r : ranking) {
+        if (shared == target_shared) break;
+        const bool receiver_free = map[r.j] == r.j && !donates[r.j];
+        const bool donor_free = map[r.i] == r.i;
+        if (!receiver_free || !donor_free) continue;
+        candidate = map;
+        candidate[r.j] = r.i;
+        if (accept && !accept(candidate.data(), L, user)) continue;   // similarity at or below threshold
+        map.swap(candidate);
+        donates[r.i] = 1;
+        ++shared;
+    }
+    std::copy(map.begin(), map.end(), share_map);
+    number_slots(share_map, L, slot_of_layer, n_slots);
+    *n_shared = shared;
+    if (shared != target_shared)
+        return fail(KVS_ERR_TARGET_UNREACHED, "ranking exhausted with %d of %d layers shared", shared, target_shared);
+    return KVS_OK;
+}
+
+size_t kvs_store_bytes(const kvs_desc* d)
+{
+    if (check_desc(d) != KVS_OK) return 0;
+    return (size_t)d->n_slots * d->num_blocks * d->Hkv * 2 * KVS_BLOCK_TOKENS * (size_t)d->head_dim *
+           elem_bytes(d->dtype);
+}
+
+int kvs_set_split_tokens(int tokens)
+{
+    if (tokens < 0 || tokens % 64 != 0) return fail(KVS_ERR_INVALID_ARG, "split tokens must be 0 or a multiple of 64");
+    g_split_tokens.store(tokens);
+    return KVS_OK;
+}
+
+size_t kvs_workspace_bytes(const kvs_desc* d, int B, int max_q_rows)
+{
+    if (check_desc(d) != KVS_OK) return 0;
+    if (B <= 0 || max_q_rows <= 0) { fail(KVS_ERR_INVALID_ARG, "B and max_q_rows must be positive"); return 0; }
+    size_t need = 0;
+    const int rows[2] = {1, max_q_rows};
+    for (int r : rows) {
+        const Split s = choose_split(d, B, r);
+        need = std::max(need, partial_floats(d, B, r, s) * sizeof(float));
+    }
+    return need + 256;   // never zero, so callers can always allocate and pass a real pointer
+}
+
+int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const void* v_new,
+                  const int32_t* start_pos, int B, int T_new, void* stream)
+{
+    if (int rc = check_store(store, layer)) return rc;
+    if (!k_new || !v_new || !start_pos) return fail(KVS_ERR_INVALID_ARG, "k_new, v_new or start_pos is NULL");
+    if (B <= 0 || T_new <= 0) return fail(KVS_ERR_INVALID_ARG, "B and T_new must be positive (B=%d, T_new=%d)", B, T_new);
+    if (T_new > store->desc.max_blocks_per_seq * KVS_BLOCK_TOKENS)
+        return fail(KVS_ERR_CAPACITY, "T_new=%d exceeds the per-sequence capacity %d", T_new,
+                    store->desc.max_blocks_per_seq * KVS_BLOCK_TOKENS);
+    if (!store->block_table && (long)B * store->desc.max_blocks_per_seq > store->desc.num_blocks)
+        return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
+    if (store->host_share_map[layer] != layer) return KVS_NOOP;   // the layer reads its donor's cache
+    kvs::CopyArgs a;
+    a.st = view_of(store, layer);
+    a.k = const_cast<void*>(k_new);
+    a.v = const_cast<void*>(v_new);
+    a.start_pos = start_pos;
+    a.t0 = 0;
+    a.B = B;
+    a.T = T_new;
+    if (int e = kvs::launch_append(a, stream)) return fail(KVS_ERR_HIP, "append launch: %s", kvs::hip_error_string(e));
+    return KVS_OK;
+}
+
+int kvs_gather_kv(const kvs_store* store, int layer, int t0, int T, int B,
+                  void* k_out, void* v_out, void* stream)
+{
+    if (int rc = check_store(store, layer)) return rc;
+    if (!k_out || !v_out) return fail(KVS_ERR_INVALID_ARG, "k_out or v_out is NULL");
+    if (B <= 0 || T <= 0 || t0 < 0) return fail(KVS_ERR_INVALID_ARG, "need B > 0, T > 0, t0 >= 0");
+    if ((long)t0 + T > (long)store->desc.max_blocks_per_seq * KVS_BLOCK_TOKENS)
+        return fail(KVS_ERR_CAPACITY, "tokens [%d, %d) exceed the per-sequence capacity", t0, t0 + T);
+    if (!store->block_table && (long)B * store->desc.max_blocks_per_seq > store->desc.num_blocks)
+        return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
+    kvs::CopyArgs a;
+    a.st = view_of(store, layer);
+    a.k = k_out;
+    a.v = v_out;
+    a.start_pos = nullptr;
+    a.t0 = t0;
+    a.B = B;
+    a.T = T;
+    if (int e = kvs::launch_gather(a, stream)) return fail(KVS_ERR_HIP, "gather launch: %s", kvs::hip_error_string(e));
+    return KVS_OK;
+}
+
+static int attention_common(const kvs_store* store, int layer, const void* q, const int32_t* lens,
+                            int lens_bias, int B, int T_new, float* out, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    if (int rc = check_store(store, layer)) return rc;
+    if (!q || !lens || !out) return fail(KVS_ERR_INVALID_ARG, "q, lengths or out is NULL");
+    if (B <= 0 || T_new <= 0) return fail(KVS_ERR_INVALID_ARG, "B and T_new must be positive (B=%d, T_new=%d)", B, T_new);
+    const kvs_desc* d = &store->desc;
+    if (T_new > d->max_blocks_per_seq * KVS_BLOCK_TOKENS)
+        return fail(KVS_ERR_CAPACITY, "T_new=%d exceeds the per-sequence capacity", T_new);
+    if (!store->block_table && (long)B * d->max_blocks_per_seq > d->num_blocks)
+        return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
+    if (B > 65535 || d->Hkv > 65535) return fail(KVS_ERR_CAPACITY, "B and Hkv are limited to 65535");
+    const Split s = choose_split(d, B, T_new);
+    const size_t need = partial_floats(d, B, T_new, s) * sizeof(float);
+    if (need > 0 && (!workspace || workspace_bytes < need))
+        return fail(KVS_ERR_INVALID_ARG, "workspace too small: need %zu bytes, got %zu", need, workspace_bytes);
+    kvs::AttnArgs a;
+    a.st = view_of(store, layer);
+    a.q = q;
+    a.lens = lens;
+    a.lens_bias = lens_bias;
+    a.B = B;
+    a.T_new = T_new;
+    a.out = out;
+    a.partials = static_cast<float*>(workspace);
+    a.pages_per_split = s.pages_per_split;
+    a.n_splits = s.n_splits;
+    if (int e = kvs::launch_attention(a, stream)) return fail(KVS_ERR_HIP, "attention launch: %s", kvs::hip_error_string(e));
+    return KVS_OK;
+}
+
+int kvs_decode_attention(const kvs_store* store, int layer, const void* q, const int32_t* seq_lens,
+                         int B, float* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return attention_common(store, layer, q, seq_lens, 0, B, 1, out, workspace, workspace_bytes, stream);
+}
+
+int kvs_prefill_attention(const kvs_store* store, int layer, const void* q, const int32_t* start_pos,
+                          int B, int T_new, float* out, void* workspace, size_t workspace_bytes,
+                          void* stream)
+{
+    return attention_common(store, layer, q, start_pos, 1, B, T_new, out, workspace, workspace_bytes, stream);
+}
+
+size_t kvs_distance_workspace_bytes(int L)
+{
+    if (L <= 0 || L > 64) { fail(KVS_ERR_UNSUPPORTED, "L must be in [1, 64]"); return 0; }
+    return kvs::distance_workspace_bytes(L);
+}
+
+int kvs_layer_distance(const void* kv_samples, int S, int L, size_t N, int dtype,
+                       float* dK2, float* dV2, float* D, void* workspace, size_t workspace_bytes,
+                       void* stream)
+{
+    if (!kv_samples || !dK2 || !dV2 || !D) return fail(KVS_ERR_INVALID_ARG, "NULL argument");
+    if (S <= 0 || L <= 0 || N == 0) return fail(KVS_ERR_INVALID_ARG, "S, L and N must be positive");
+    if (L > 64) return fail(KVS_ERR_UNSUPPORTED, "L=%d: at most 64 layers are supported", L);
+    if (dtype != KVS_F32 && dtype != KVS_BF16) return fail(KVS_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    if (N % 8 != 0) return fail(KVS_ERR_UNSUPPORTED, "N must be a multiple of 8 (got %zu)", N);
+    if ((size_t)S * L * 2 > ((size_t)1 << 62) / N) return fail(KVS_ERR_CAPACITY, "input too large");
+    const size_t need = kvs::distance_workspace_bytes(L);
+    if (!workspace || workspace_bytes < need)
+        return fail(KVS_ERR_INVALID_ARG, "workspace too small: need %zu bytes, got %zu", need, workspace_bytes);
+    if (int e = kvs::launch_layer_distance(kv_samples, S, L, N, dtype, dK2, dV2, D, workspace, stream))
+        return fail(KVS_ERR_HIP, "distance launch: %s", kvs::hip_error_string(e));
+    return KVS_OK;
+}
+
+}  // extern "C"

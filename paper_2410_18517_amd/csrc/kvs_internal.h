@@ -1,0 +1,45 @@
+// Internal interface between the host-side C ABI (kvs_host.cpp) and the kernel launchers
+// (*.hip).  Plain structs only; nothing here is visible to callers of the library.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+
+namespace kvs {
+
+struct StoreView {
+    void* pool;
+    const int32_t* share_map;      // device [L]
+    const int32_t* slot_of_layer;  // device [L]
+    const int32_t* block_table;    // device [B][max_blocks_per_seq] or nullptr (contiguous)
+    int32_t layer, L, n_slots, Hq, Hkv, head_dim, dtype, num_blocks, max_blocks_per_seq;
+};
+
+struct AttnArgs {
+    StoreView st;
+    const void* q;          // device [B][T_new][Hq][D], store dtype
+    const int32_t* lens;    // device [B]: decode: tokens in the cache; prefill: position of row 0
+    int32_t lens_bias;      // 0 for decode (row r sees lens + r keys), 1 for prefill
+    int32_t B, T_new;
+    float* out;             // device fp32 [B][T_new][Hq][D]
+    float* partials;        // device fp32 [B][T_new][Hq][n_splits][D + 2]
+    int32_t pages_per_split, n_splits;
+};
+
+struct CopyArgs {
+    StoreView st;
+    void* k;                // device [B][T][Hkv][D]
+    void* v;
+    const int32_t* start_pos;  // device [B] (append) or nullptr (gather: t0 for all)
+    int32_t t0, B, T;
+};
+
+// Each returns hipError_t as int (0 = success) after enqueueing on `stream`.
+int launch_append(const CopyArgs& a, void* stream);
+int launch_gather(const CopyArgs& a, void* stream);
+int launch_attention(const AttnArgs& a, void* stream);
+int launch_layer_distance(const void* kv, int S, int L, size_t N, int dtype, float* dK2, float* dV2,
+                          float* D, void* workspace, void* stream);
+size_t distance_workspace_bytes(int L);
+const char* hip_error_string(int err);
+
+}  // namespace kvs

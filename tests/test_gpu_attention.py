@@ -1,0 +1,140 @@
+"""GPU parity: decode and causal-prefill attention over the shared store vs the fp64 oracle.
+
+Tolerance (both stores): every output vector within 5e-3 relative L2 of the oracle; fp32 stores
+are held to 1e-5.  Edge cases: empty, one-token, page-boundary and ragged lengths, one and many
+context splits, recipients (incl. the last layer), donors with several recipients."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as orc
+from paper_2410_18517_amd import inputs
+from helpers import Case, rel_l2_rows, REL_L2_ATTENTION
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kb():
+    from paper_2410_18517_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    yield binding
+    binding.kvs_set_split_tokens(0)
+
+
+def _check_decode(kb, case, layers, seq_lens, tol):
+    seq_lens = np.asarray(seq_lens, np.int32)
+    worst = 0.0
+    for layer in layers:
+        q = case.q(layer)
+        got = kb.kvs_decode_attention(case.store, layer, q.cuda(), seq_lens).cpu().numpy()
+        want = orc.decode_attention(layer, case.share_map, case.K, case.V, inputs.to_oracle_array(q), seq_lens)
+        assert np.isfinite(got).all()
+        err = rel_l2_rows(got, want)
+        worst = max(worst, err.max())
+        assert err.max() <= tol, (layer, err.max())
+    return worst
+
+
+def test_tiny_config_fp32(kb):
+    """4 layers, 4 query / 2 kv heads, d 64, one sequence of 128 tokens, fp32, layer 3 reads layer 1."""
+    w = inputs.WORKLOADS["tiny"]
+    share = inputs.make_share_map(w.L, w.n_shared, fixed=w.fixed_map)
+    for paged in (True, False):
+        case = Case(kb, w.L, w.Hq, w.Hkv, w.d, w.B, "f32", w.context, share, paged=paged, seed=1)
+        assert case.store.desc.n_slots == 3
+        _check_decode(kb, case, range(w.L), [w.context], 1e-5)
+        # the recipient's output is attention over the donor's cache, not a cache of its own
+        q3 = case.q(3)
+        got = kb.kvs_decode_attention(case.store, 3, q3.cuda(), np.array([128], np.int32)).cpu().numpy()
+        ident = np.arange(4, dtype=np.int32)
+        want = orc.decode_attention(1, ident, case.K, case.V, inputs.to_oracle_array(q3), [128])
+        assert rel_l2_rows(got, want).max() <= 1e-5
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp32_ragged_and_gqa(kb, d):
+    share = np.array([0, 0, 2, 2, 0], np.int32)               # layer 0 serves two recipients
+    case = Case(kb, 5, 6, 2, d, 4, "f32", 150, share, seed=5)
+    _check_decode(kb, case, range(5), [150, 0, 1, 77], 1e-5)
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(4, 4, 128), (8, 2, 128), (12, 2, 128), (16, 1, 128), (6, 2, 64), (5, 5, 64)])
+def test_bf16_decode_shapes(kb, Hq, Hkv, d):
+    L = 6
+    share = np.array([0, 1, 0, 3, 1, 3], np.int32)            # last layer is a recipient
+    case = Case(kb, L, Hq, Hkv, d, 3, "bf16", 400, share, seed=Hq * 10 + Hkv)
+    _check_decode(kb, case, range(L), [400, 123, 257], REL_L2_ATTENTION)
+
+
+@pytest.mark.parametrize("split_tokens", [0, 64, 128, 512])
+def test_bf16_edge_lengths_and_splits(kb, split_tokens):
+    kb.kvs_set_split_tokens(split_tokens)
+    try:
+        share = np.array([0, 1, 1], np.int32)
+        lens = [0, 1, 15, 16, 17, 63, 64, 65, 300, 333]
+        case = Case(kb, 3, 8, 2, 128, len(lens), "bf16", 333, share, seed=21)
+        _check_decode(kb, case, range(3), lens, REL_L2_ATTENTION)
+        # lengths above the capacity are clamped to it
+        q = case.q(0)
+        a = kb.kvs_decode_attention(case.store, 0, q.cuda(), np.full(len(lens), 10 ** 6, np.int32))
+        b = kb.kvs_decode_attention(case.store, 0, q.cuda(), np.full(len(lens), 336, np.int32))
+        assert torch.equal(a, b)
+    finally:
+        kb.kvs_set_split_tokens(0)
+
+
+def test_bf16_unwritten_tail_cannot_leak(kb):
+    """Rows past seq_len hold NaN bit patterns: they must not reach the output."""
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, 2, 4, 2, 128, 2, "bf16", 64, share, seed=8, fill_tokens=64)
+    junk = torch.full((2, 64, 2, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    kb.kvs_append_kv(case.store, 0, junk[:, :43].contiguous(), junk[:, :43].contiguous(), np.array([21, 21], np.int32))
+    case.K[0] = case.K[0][:, :21]; case.V[0] = case.V[0][:, :21]
+    _check_decode(kb, case, [0, 1], [21, 9], REL_L2_ATTENTION)
+
+
+def test_decode_step_order_recipient_sees_current_token(kb):
+    """One whole decode step: layers in order, own-cache layers append then attend, recipients
+    attend to a donor that already holds this step's token."""
+    L, Hq, Hkv, d, B = 5, 8, 2, 128, 3
+    share = np.array([0, 1, 0, 1, 4], np.int32)
+    lens0 = np.array([40, 7, 16], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, "bf16", 48, share, seed=31, fill_tokens=40)
+    Ko = [None if x is None else np.concatenate([x, np.zeros((B, 8, Hkv, d), x.dtype)], 1) for x in case.K]
+    Vo = [None if x is None else np.concatenate([x, np.zeros((B, 8, Hkv, d), x.dtype)], 1) for x in case.V]
+    for step in range(2):
+        lens = lens0 + step + 1
+        for layer in range(L):
+            k_new = inputs.normal((B, 1, Hkv, d), 31, layer, step, 70)
+            v_new = inputs.normal((B, 1, Hkv, d), 31, layer, step, 71)
+            st = kb.kvs_append_kv(case.store, layer, k_new.cuda(), v_new.cuda(), lens - 1)
+            wrote = orc.append_kv(layer, share, Ko, Vo, inputs.to_oracle_array(k_new), inputs.to_oracle_array(v_new), lens - 1)
+            assert (st == kb.KVS_OK) == wrote and (st == kb.KVS_NOOP) == (share[layer] != layer)
+            q = inputs.normal((B, Hq, d), 31, layer, step, 72)
+            got = kb.kvs_decode_attention(case.store, layer, q.cuda(), lens).cpu().numpy()
+            want = orc.decode_attention(layer, share, Ko, Vo, inputs.to_oracle_array(q), lens)
+            assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,T_new", [("bf16", 4, 4, 128, 64), ("bf16", 8, 2, 128, 21),
+                                                  ("bf16", 6, 1, 64, 33), ("f32", 4, 2, 64, 9)])
+def test_causal_prefill(kb, dtype, Hq, Hkv, d, T_new):
+    L, B, cap = 3, 3, 200
+    share = np.array([0, 0, 2], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, dtype, cap, share, seed=41)
+    tol = 1e-5 if dtype == "f32" else REL_L2_ATTENTION
+    for start in ([0, 0, 0], [cap - T_new, 5, 100]):
+        start = np.asarray(start, np.int32)
+        for layer in range(L):
+            q = case.q(layer, rows=T_new)
+            got = kb.kvs_prefill_attention(case.store, layer, q.cuda(), start).cpu().numpy()
+            want = orc.shared_attention(layer, share, case.K, case.V, inputs.to_oracle_array(q), start)
+            assert np.isfinite(got).all()
+            assert rel_l2_rows(got, want).max() <= tol, (layer, start)
+    # the last prefill row is what the following decode step computes
+    q = case.q(0, rows=T_new)
+    pre = kb.kvs_prefill_attention(case.store, 0, q.cuda(), np.array([10, 20, 30], np.int32))
+    dec = kb.kvs_decode_attention(case.store, 0, q[:, -1].contiguous().cuda(),
+                                  np.array([10, 20, 30], np.int32) + T_new)
+    assert rel_l2_rows(dec.cpu().numpy(), pre[:, -1].cpu().numpy().astype(np.float64)).max() <= 2e-3

@@ -1,0 +1,146 @@
+"""CPU-only checks of libkvs.so: exported symbols, the strategy walk (bit-exact against the
+oracle on the same distance matrix) and every argument error that is decided before a HIP call."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import share_map as osm
+from paper_2410_18517_amd import binding as kb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "kvs.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", body))
+    declared -= {"kvs_accept_fn"}
+    assert declared == set(kb.EXPORTS)
+    lib = kb.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("L,C_", [(4, 1), (8, 3), (32, 8), (40, 12), (48, 14), (48, 18)])
+@pytest.mark.parametrize("order", [0, 1])
+def test_share_map_matches_oracle_bitwise(L, C_, order):
+    rng = np.random.default_rng(L * 100 + C_)
+    A = rng.random((L, L)).astype(np.float32)
+    D = A + A.T
+    np.fill_diagonal(D, 0)
+    D[1, 3] = D[3, 1] = D[0, 2] = D[2, 0] = 0.5          # a tie
+    st, share, slot, n_slots, n_shared = kb.kvs_build_share_map(D, C_, order)
+    ost, oshare, oslot, on_slots, on_shared = osm.build_share_map(D, L, C_, ascending=bool(order))
+    assert (st, share.tolist(), slot.tolist(), n_slots, n_shared) == (ost, oshare, oslot, on_slots, on_shared)
+    assert kb.kvs_validate_share_map(share) == kb.KVS_OK
+    s2, n2 = kb.kvs_slots_from_share_map(share)
+    assert s2.tolist() == oslot and n2 == on_slots
+
+
+def test_share_map_accept_callback_and_unreachable_target():
+    D = np.array([[0, 1, 7, 8], [1, 0, 6, 9], [7, 6, 0, 5], [8, 9, 5, 0]], np.float32)
+    calls = []
+    def accept(m):
+        calls.append(list(m))
+        return len(calls) != 1                       # discard the first candidate only
+    got = kb.kvs_build_share_map(D, 2, 0, accept)
+    ocalls = []
+    def oaccept(m):
+        ocalls.append(list(m))
+        return len(ocalls) != 1
+    want = osm.build_share_map(D, 4, 2, accept=oaccept)
+    assert calls == ocalls == [[0, 1, 2, 1], [0, 1, 2, 0], [0, 1, 0, 0]]
+    assert (got[0], got[1].tolist(), got[2].tolist(), got[3], got[4]) == want
+    st, share, _, n_slots, n_shared = kb.kvs_build_share_map(D, 3, 0, lambda m: False)
+    assert st == kb.KVS_ERR_TARGET_UNREACHED and n_shared == 0 and share.tolist() == [0, 1, 2, 3] and n_slots == 4
+    assert "exhausted" in kb.last_error()
+
+
+def test_share_map_argument_errors():
+    D = np.zeros((3, 3), np.float32)
+    with pytest.raises(kb.KvsError) as e:
+        kb.kvs_build_share_map(D, 3)
+    assert e.value.status == kb.KVS_ERR_INVALID_ARG
+    D[0, 2] = np.nan
+    with pytest.raises(kb.KvsError):
+        kb.kvs_build_share_map(D, 1)
+    with pytest.raises(kb.KvsError):
+        kb.kvs_build_share_map(np.zeros((3, 3), np.float32), 1, order=2)
+    assert kb.kvs_validate_share_map([0, 0, 1]) == kb.KVS_ERR_BAD_MAP      # chain
+    assert kb.kvs_validate_share_map([1, 1]) == kb.KVS_ERR_BAD_MAP         # donor nearer the output
+    assert kb.kvs_validate_share_map([0, 0, 0, 3]) == kb.KVS_OK
+
+
+def _desc(**kw):
+    base = dict(L=4, n_slots=3, Hq=4, Hkv=2, head_dim=128, dtype=kb.KVS_BF16, block_tokens=16,
+                num_blocks=8, max_blocks_per_seq=4)
+    base.update(kw)
+    return kb.kvs_desc(**base)
+
+
+def test_store_and_workspace_sizes():
+    lib = kb.lib()
+    d = _desc()
+    assert lib.kvs_store_bytes(C.byref(d)) == 3 * 8 * 2 * 2 * 16 * 128 * 2
+    assert lib.kvs_store_bytes(C.byref(_desc(dtype=kb.KVS_F32, head_dim=64))) == 3 * 8 * 2 * 2 * 16 * 64 * 4
+    assert lib.kvs_workspace_bytes(C.byref(d), 2, 1) > 0
+    for bad in (dict(head_dim=96), dict(block_tokens=32), dict(Hq=5), dict(n_slots=5), dict(dtype=7),
+                dict(Hq=34, Hkv=2), dict(num_blocks=0), dict(dtype=kb.KVS_F32, head_dim=320)):
+        assert lib.kvs_store_bytes(C.byref(_desc(**bad))) == 0, bad
+        assert kb.last_error()
+    assert lib.kvs_workspace_bytes(C.byref(d), 0, 1) == 0
+    assert lib.kvs_distance_workspace_bytes(65) == 0 and lib.kvs_distance_workspace_bytes(48) > 0
+
+
+def _fake_store(share=(0, 1, 2, 1), slots=(0, 1, 2, 1), **kw):
+    """A store whose device pointers are junk: valid only for calls that fail before any launch."""
+    hs, hl = np.asarray(share, np.int32), np.asarray(slots, np.int32)
+    st = kb.kvs_store(_desc(**kw), 0x1000, 0x1000, 0x1000, None, hs.ctypes.data, hl.ctypes.data)
+    st._keep = (hs, hl)
+    return st
+
+
+def test_entry_points_reject_bad_arguments_without_touching_the_gpu():
+    lib = kb.lib()
+    st = _fake_store()
+    p = C.c_void_p(0x1000)
+    # append on a recipient layer is a no-op decided on the host
+    assert lib.kvs_append_kv(C.byref(st), 3, p, p, p, 1, 1, None) == kb.KVS_NOOP
+    assert lib.kvs_append_kv(C.byref(st), 4, p, p, p, 1, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_append_kv(C.byref(st), -1, p, p, p, 1, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_append_kv(C.byref(st), 0, None, p, p, 1, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_append_kv(C.byref(st), 0, p, p, p, 1, 0, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_append_kv(C.byref(st), 0, p, p, p, 1, 65, None) == kb.KVS_ERR_CAPACITY
+    assert lib.kvs_append_kv(C.byref(st), 0, p, p, p, 3, 1, None) == kb.KVS_ERR_CAPACITY   # contiguous: 3*4 > 8 blocks
+    assert lib.kvs_append_kv(None, 0, p, p, p, 1, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_attention(C.byref(st), 0, None, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_attention(C.byref(st), 9, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_attention(C.byref(st), 0, p, p, 0, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_prefill_attention(C.byref(st), 0, p, p, 1, 65, p, p, 1 << 30, None) == kb.KVS_ERR_CAPACITY
+    assert lib.kvs_gather_kv(C.byref(st), 0, 60, 8, 1, p, p, None) == kb.KVS_ERR_CAPACITY
+    assert lib.kvs_gather_kv(C.byref(st), 0, 0, 8, 1, None, p, None) == kb.KVS_ERR_INVALID_ARG
+    # maps: chain, forward donor, slot disagreement, slot out of range
+    for share, slots in (((0, 0, 1, 3), (0, 0, 0, 1)), ((1, 1, 2, 3), (0, 0, 1, 2)),
+                         ((0, 1, 2, 1), (0, 1, 2, 2)), ((0, 1, 2, 1), (0, 1, 3, 1))):
+        bad = _fake_store(share, slots)
+        assert lib.kvs_decode_attention(C.byref(bad), 0, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_BAD_MAP
+    assert lib.kvs_decode_attention(C.byref(_fake_store(head_dim=96)), 0, p, p, 1, p, p, 1 << 30, None) \
+        == kb.KVS_ERR_UNSUPPORTED
+    # split workspace too small (4 blocks per sequence, forced 64-token splits => 1 split... use more blocks)
+    big = _fake_store(max_blocks_per_seq=64, num_blocks=64)
+    assert lib.kvs_set_split_tokens(64) == kb.KVS_OK
+    try:
+        assert lib.kvs_decode_attention(C.byref(big), 0, p, p, 1, p, p, 16, None) == kb.KVS_ERR_INVALID_ARG
+        assert "workspace" in kb.last_error()
+    finally:
+        assert lib.kvs_set_split_tokens(0) == kb.KVS_OK
+    assert lib.kvs_set_split_tokens(100) == kb.KVS_ERR_INVALID_ARG
+    # distance
+    assert lib.kvs_layer_distance(None, 1, 2, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_layer_distance(p, 1, 65, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
+    assert lib.kvs_layer_distance(p, 1, 2, 12, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
+    assert lib.kvs_layer_distance(p, 0, 2, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_layer_distance(p, 1, 2, 8, 0, p, p, p, p, 16, None) == kb.KVS_ERR_INVALID_ARG
