@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the shared-KV decode hot path on one MI355X.
+
+A step is one decode step of the whole model: for every layer in order, kvs_append_kv (a no-op
+for layers that read a donor's cache) followed by kvs_decode_attention over the slot the
+layer's share-map entry resolves to.  Inputs are synthetic (seeded N(0,1), bf16) and resident in
+HBM before timing starts.  Prints one JSON line: tokens/s (batch size / step time), the HBM
+roofline of the decode-attention launch, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes_per_launch(w, seq_lens):
+    """Bytes one decode-attention launch must move: every stored key and value of the layer's
+    slot once, q in, fp32 out, and the page-table entries that address the context."""
+    e = 2 if w.dtype == "bf16" else 4
+    kv = int(seq_lens.astype(np.int64).sum()) * w.Hkv * w.d * 2 * e
+    qo = w.B * w.Hq * w.d * (e + 4)
+    table = int(((seq_lens.astype(np.int64) + 15) // 16).sum()) * 4
+    return kv + qo + table
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3-8b-32k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--split-tokens", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this path has no multi-GPU part (run with --gpus 1)")
+
+    import torch
+    from paper_2410_18517_amd import binding as kb, inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    w = inputs.WORKLOADS[args.workload]
+    if args.split_tokens:
+        kb.kvs_set_split_tokens(args.split_tokens)
+
+    share = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)
+    seq_lens = inputs.make_seq_lens(w, 1)
+    max_blocks = w.max_blocks_per_seq
+    num_blocks = w.B * max_blocks
+    table = inputs.make_block_table(w.B, max_blocks, num_blocks, 1)
+    store = kb.KVStore(share, w.Hq, w.Hkv, w.d, w.dtype, num_blocks, max_blocks, block_table=table)
+    tdt = store.torch_dtype
+
+    # fill every slot through the library's own append path; keep one layer's source rows for the oracle
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_BASE)
+    own = [l for l in range(w.L) if share[l] == l]
+    sample_layer = next(l for l in range(w.L) if share[l] != l)          # a recipient: exercises the map
+    donor = int(share[sample_layer])
+    zeros = torch.zeros(w.B, dtype=torch.int32, device=dev)
+    kept = None
+    for l in own:
+        k = torch.randn((w.B, w.context, w.Hkv, w.d), device=dev, dtype=torch.float32, generator=gen).to(tdt)
+        v = torch.randn((w.B, w.context, w.Hkv, w.d), device=dev, dtype=torch.float32, generator=gen).to(tdt)
+        assert kb.kvs_append_kv(store, l, k, v, zeros) == kb.KVS_OK
+        if l == donor:
+            kept = (k.cpu(), v.cpu())
+        del k, v
+    q = [torch.randn((w.B, w.Hq, w.d), device=dev, dtype=torch.float32, generator=gen).to(tdt) for _ in range(w.L)]
+    k_new = torch.randn((w.B, 1, w.Hkv, w.d), device=dev, dtype=torch.float32, generator=gen).to(tdt)
+    v_new = torch.randn((w.B, 1, w.Hkv, w.d), device=dev, dtype=torch.float32, generator=gen).to(tdt)
+    lens_dev = torch.from_numpy(seq_lens).to(dev)
+    pos_dev = lens_dev - 1
+    # this step's token of the sampled donor layer, so the oracle sees what the store holds
+    if kept is not None:
+        for b in range(w.B):
+            kept[0][b, seq_lens[b] - 1] = k_new[b, 0].cpu()
+            kept[1][b, seq_lens[b] - 1] = v_new[b, 0].cpu()
+    out = torch.empty((w.L, w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    ws = store.workspace(w.B, 1)
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        for l in range(w.L):
+            kb.kvs_append_kv(store, l, k_new, v_new, pos_dev)
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            kb.kvs_decode_attention(store, l, q[l], lens_dev, out=out[l], workspace=ws)
+            if events is not None:
+                e1.record()
+                events.append((e0, e1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = w.B / (ms_per_step * 1e-3)
+
+    launch_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+    alg_bytes = algorithmic_bytes_per_launch(w, seq_lens)
+    achieved = alg_bytes / (launch_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "attn_bf16_kernel (+ split combine)", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": None, "launch_us": round(launch_ms * 1e3, 2), "algorithmic_bytes": alg_bytes}
+
+    result = {
+        "metric": "shared-KV decode attention tokens/s", "value": round(tokens_per_s, 2), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "layers": w.L, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
+                   "batch": w.B, "context": w.context if w.min_context is None else [w.min_context, w.context],
+                   "page_tokens": 16, "shared_layers": w.n_shared, "kv_slots": int(store.desc.n_slots)},
+        "hbm_gbps": round(alg_bytes * w.L / (ms_per_step * 1e-3) / 1e9, 1),
+        "hbm_frac": round(alg_bytes * w.L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline and kept is not None:
+        from oracle import attention as orc
+        K = [None] * w.L
+        V = [None] * w.L
+        K[donor], V[donor] = inputs.to_oracle_array(kept[0]), inputs.to_oracle_array(kept[1])
+        qs = inputs.to_oracle_array(q[sample_layer])
+        c0 = time.perf_counter()
+        want = orc.decode_attention(sample_layer, share, K, V, qs, seq_lens)
+        c1 = time.perf_counter()
+        got = out[sample_layer].cpu().numpy().astype(np.float64)
+        err = float((np.sqrt(((got - want) ** 2).sum(-1)) / np.sqrt((want ** 2).sum(-1))).max())
+        layer_s = c1 - c0
+        result["cpu_baseline"] = {
+            "value": round(w.B / (layer_s * w.L), 4), "unit": "tokens/s", "cores": orc.num_threads(),
+            "kind": "oracle",
+            "sample": f"fp64 oracle, decode attention of 1 of {w.L} layers (layer {sample_layer}, reads layer "
+                      f"{donor}'s cache), all {w.B} sequences x {w.Hq} heads at full context: {layer_s:.2f} s; "
+                      f"tokens/s = batch / (that x {w.L} layers)"}
+        result["parity_rel_l2_sample"] = err
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

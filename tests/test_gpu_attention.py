@@ -90,7 +90,7 @@ def test_bf16_unwritten_tail_cannot_leak(kb):
     case = Case(kb, 2, 4, 2, 128, 2, "bf16", 64, share, seed=8, fill_tokens=64)
     junk = torch.full((2, 64, 2, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
     kb.kvs_append_kv(case.store, 0, junk[:, :43].contiguous(), junk[:, :43].contiguous(), np.array([21, 21], np.int32))
-    case.K[0] = case.K[0][:, :21]; case.V[0] = case.V[0][:, :21]
+    case.K[0] = np.ascontiguousarray(case.K[0][:, :21]); case.V[0] = np.ascontiguousarray(case.V[0][:, :21])
     _check_decode(kb, case, [0, 1], [21, 9], REL_L2_ATTENTION)
 
 
