@@ -21,6 +21,7 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int resolve_slot(const StoreView& st)
 {
@@ -204,7 +205,8 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a)
 // straight into MFMA operand registers (the store's in-page order is the operand order) with
 // kPrefetch pages in flight, and keeps a private online-softmax state.  The states merge
 // through LDS at the end; with more than one split the merged, unnormalised state goes to
-// the partials buffer for the combine kernel.
+// the partials buffer, and the last workgroup to finish a (sequence, kv head, column group)
+// folds its splits into the output.
 //
 // MFMA roles.  Scores: S[token][column] = K_page(16 x D) . Q^T(D x 16) with
 // v_mfma_f32_16x16x32_bf16; lane l holds the scores of column l%16 for tokens 4*(l/16)..+3,
@@ -220,18 +222,37 @@ struct PageRegs {
 template <int D>
 __device__ __forceinline__ void load_page(PageRegs<D>& r, const unsigned short* pool, size_t page_off, int lane)
 {
-    const uint4* kp = reinterpret_cast<const uint4*>(pool + page_off) + lane;
-    const uint4* vp = kp + (kPageTokens * D * 2) / 16;
+    // Every key and value is read once per launch: stream them past the caches.
+    const u32x4* kp = reinterpret_cast<const u32x4*>(pool + page_off) + lane;
+    const u32x4* vp = kp + (kPageTokens * D * 2) / 16;
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) r.k[s] = kp[s * 64];
+    for (int s = 0; s < D / 32; ++s) r.k[s] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(kp + s * 64));
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) r.v[s] = vp[s * 64];
+    for (int s = 0; s < D / 32; ++s) r.v[s] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(vp + s * 64));
 }
 
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
 {
     floatx2 f = {lo, hi};
     return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
+}
+
+// Split states cross compute units, and on this chip each group of compute units has its own
+// L2.  They are therefore written and read with device-scope atomic accesses, which go to
+// the memory side of the L2s, instead of flushing and invalidating whole caches around
+// ordinary accesses.  A writer waits for its stores to complete before its workgroup bumps
+// the arrival counter; the reader issues its loads only after it has read the final count.
+__device__ __forceinline__ void publish_pair(float* p, float x, float y)
+{
+    const floatx2 v = {x, y};
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), __builtin_bit_cast(unsigned long long, v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ floatx2 fetch_pair(const float* p)
+{
+    const unsigned long long w = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_bit_cast(floatx2, w);
 }
 
 template <int D, int NT>
@@ -424,34 +445,60 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             } else {
                 float* part = a.partials + (row * a.n_splits + split) * (size_t)(D + 2);
                 // (D + 2) floats per record keeps 8-byte alignment only: store as pairs
-                *reinterpret_cast<floatx2*>(part + d4) = floatx2{acc[0], acc[1]};
-                *reinterpret_cast<floatx2*>(part + d4 + 2) = floatx2{acc[2], acc[3]};
-                if (d4 == 0) *reinterpret_cast<floatx2*>(part + D) = floatx2{M, lt};
+                publish_pair(part + d4, acc[0], acc[1]);
+                publish_pair(part + d4 + 2, acc[2], acc[3]);
+                if (d4 == 0) publish_pair(part + D, M, lt);
             }
         }
     }
-}
+    if (a.n_splits == 1) return;
 
-// Merge the per-split states of one output row: grid (Hq, T_new, B), D threads.
-template <int D>
-__global__ __launch_bounds__(D) void combine_kernel(AttnArgs a)
-{
-    const int h = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
-    const size_t row = ((size_t)b * a.T_new + r) * a.st.Hq + h;
-    const float* part = a.partials + row * a.n_splits * (size_t)(D + 2);
-    float M = -INFINITY;
-    for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, part[s * (D + 2) + D]);
-    const float M_use = M == -INFINITY ? 0.f : M;
-    float acc = 0.f, lt = 0.f;
-    for (int s = 0; s < a.n_splits; ++s) {
-        const float* ps = part + s * (D + 2);
-        const float wgt = __builtin_amdgcn_exp2f(ps[D] - M_use);
-        if (wgt > 0.f) {                      // empty splits carry m = -inf and are skipped
-            acc += wgt * ps[threadIdx.x];
-            lt += wgt * ps[D + 1];
-        }
+    // The workgroup that arrives last at this (sequence, kv head, column group) merges the
+    // splits.  Nobody waits: each workgroup publishes its partial state, bumps the counter
+    // and leaves; the one that reads n_splits - 1 finds every other state already published.
+    __shared__ int s_is_last;
+    // vmcnt(0): every device-scope store this wavefront issued has been acknowledged.  A
+    // workgroup-scope fence would not wait for that (the compute unit orders its own accesses).
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int n_col_groups = gridDim.x / a.n_splits;
+        int* counter = a.counters + ((size_t)b * st.Hkv + g) * n_col_groups + cgrp;
+        const int arrived = atomicAdd(counter, 1);
+        s_is_last = arrived == a.n_splits - 1;
+        if (s_is_last) atomicExch(counter, 0);          // leave the counter ready for the next call
     }
-    a.out[row * D + threadIdx.x] = lt > 0.f ? acc / lt : 0.f;
+    __syncthreads();
+    if (!s_is_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    const int wg_cols = NT * 16;
+    for (int idx = threadIdx.x; idx < wg_cols * (D / 4); idx += kThreads) {
+        const int cidx = cgrp * wg_cols + idx / (D / 4);
+        const int d4 = (idx % (D / 4)) * 4;
+        if (cidx >= ncols) break;
+        const int r = cidx / group, hc = cidx % group;
+        const size_t row = ((size_t)b * a.T_new + r) * st.Hq + g * group + hc;
+        const float* part = a.partials + row * a.n_splits * (size_t)(D + 2);
+        float M = -INFINITY;
+#pragma unroll 8
+        for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, fetch_pair(part + s * (D + 2) + D)[0]);
+        const float M_use = M == -INFINITY ? 0.f : M;
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        float lt = 0.f;
+#pragma unroll 4
+        for (int s = 0; s < a.n_splits; ++s) {
+            const float* ps = part + s * (D + 2);
+            const floatx2 ml = fetch_pair(ps + D);
+            const floatx2 lo = fetch_pair(ps + d4);
+            const floatx2 hi = fetch_pair(ps + d4 + 2);
+            const float wgt = __builtin_amdgcn_exp2f(ml[0] - M_use);   // empty splits carry m = -inf
+            acc += wgt * floatx4{lo[0], lo[1], hi[0], hi[1]};
+            lt += wgt * ml[1];
+        }
+        const float inv = lt > 0.f ? 1.f / lt : 0.f;
+        *reinterpret_cast<floatx4*>(a.out + row * D + d4) = acc * inv;
+    }
 }
 
 template <int D>
@@ -467,11 +514,6 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
         hipLaunchKernelGGL((attn_bf16_kernel<D, 4>), grid, dim3(kThreads), 0, s, a);
     }
     if (hipError_t e = hipGetLastError()) return (int)e;
-    if (a.n_splits > 1) {
-        dim3 grid(a.st.Hq, a.T_new, a.B);
-        hipLaunchKernelGGL((combine_kernel<D>), grid, dim3(D), 0, s, a);
-        if (hipError_t e = hipGetLastError()) return (int)e;
-    }
     return 0;
 }
 

@@ -31,7 +31,7 @@ std::atomic<int> g_split_tokens{0};
 
 // Workgroups the decode grid should at least reach: 256 compute units, several resident
 // workgroups each, and enough left over that ragged batches even out.
-constexpr int kTargetWorkgroups = 2048;
+constexpr int kTargetWorkgroups = 512;
 constexpr int kMinPagesPerSplit = 4;   // one page per wavefront of the workgroup
 
 int check_desc(const kvs_desc* d)
@@ -157,6 +157,14 @@ Split choose_split(const kvs_desc* d, int B, int T_new)
     return s;
 }
 
+// Workspace layout: arrival counters first (they must start, and are left, at zero), then
+// the per-split partial states.
+size_t counter_bytes(const kvs_desc* d, int B, const Split& s)
+{
+    const size_t n = (size_t)B * d->Hkv * s.n_col_groups * sizeof(int32_t);
+    return (n + 255) / 256 * 256;
+}
+
 size_t partial_floats(const kvs_desc* d, int B, int T_new, const Split& s)
 {
     if (s.n_splits <= 1) return 0;
@@ -251,9 +259,9 @@ size_t kvs_workspace_bytes(const kvs_desc* d, int B, int max_q_rows)
     const int rows[2] = {1, max_q_rows};
     for (int r : rows) {
         const Split s = choose_split(d, B, r);
-        need = std::max(need, partial_floats(d, B, r, s) * sizeof(float));
+        need = std::max(need, counter_bytes(d, B, s) + partial_floats(d, B, r, s) * sizeof(float));
     }
-    return need + 256;   // never zero, so callers can always allocate and pass a real pointer
+    return need;
 }
 
 int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const void* v_new,
@@ -316,8 +324,8 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
         return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
     if (B > 65535 || d->Hkv > 65535) return fail(KVS_ERR_CAPACITY, "B and Hkv are limited to 65535");
     const Split s = choose_split(d, B, T_new);
-    const size_t need = partial_floats(d, B, T_new, s) * sizeof(float);
-    if (need > 0 && (!workspace || workspace_bytes < need))
+    const size_t need = counter_bytes(d, B, s) + partial_floats(d, B, T_new, s) * sizeof(float);
+    if (!workspace || workspace_bytes < need)
         return fail(KVS_ERR_INVALID_ARG, "workspace too small: need %zu bytes, got %zu", need, workspace_bytes);
     kvs::AttnArgs a;
     a.st = view_of(store, layer);
@@ -327,7 +335,8 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     a.B = B;
     a.T_new = T_new;
     a.out = out;
-    a.partials = static_cast<float*>(workspace);
+    a.counters = static_cast<int32_t*>(workspace);
+    a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(d, B, s));
     a.pages_per_split = s.pages_per_split;
     a.n_splits = s.n_splits;
     if (int e = kvs::launch_attention(a, stream)) return fail(KVS_ERR_HIP, "attention launch: %s", kvs::hip_error_string(e));

@@ -22,6 +22,7 @@ struct AttnArgs {
     int32_t B, T_new;
     float* out;             // device fp32 [B][T_new][Hq][D]
     float* partials;        // device fp32 [B][T_new][Hq][n_splits][D + 2]
+    int32_t* counters;      // device [B][Hkv][n_col_groups], zero between calls
     int32_t pages_per_split, n_splits;
 };
 

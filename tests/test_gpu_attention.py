@@ -84,6 +84,29 @@ def test_bf16_edge_lengths_and_splits(kb, split_tokens):
         kb.kvs_set_split_tokens(0)
 
 
+def test_many_splits_merge_is_exact_and_repeatable(kb):
+    """128 splits per (sequence, kv head): the merge by the last-arriving workgroup must see every
+    split's state.  The merge order is fixed, so repeated calls agree bit for bit."""
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, 2, 8, 2, 128, 6, "bf16", 8192, share, seed=17)
+    lens = np.array([8192, 8000, 4097, 64, 1, 0], np.int32)
+    try:
+        kb.kvs_set_split_tokens(64)
+        q = case.q(1)
+        want = orc.decode_attention(1, share, case.K, case.V, inputs.to_oracle_array(q), lens)
+        first = None
+        for _ in range(25):
+            got = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens)
+            first = got.clone() if first is None else first
+            assert torch.equal(got, first)
+        assert rel_l2_rows(first.cpu().numpy(), want).max() <= REL_L2_ATTENTION
+        kb.kvs_set_split_tokens(8192)                                    # one split: no merge at all
+        single = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens).cpu().numpy()
+        assert rel_l2_rows(single, want).max() <= REL_L2_ATTENTION
+    finally:
+        kb.kvs_set_split_tokens(0)
+
+
 def test_bf16_unwritten_tail_cannot_leak(kb):
     """Rows past seq_len hold NaN bit patterns: they must not reach the output."""
     share = np.array([0, 0], np.int32)
