@@ -29,9 +29,11 @@ int fail(int code, const char* fmt, ...)
 
 std::atomic<int> g_split_tokens{0};
 
-// Workgroups the decode grid should at least reach: 256 compute units, several resident
-// workgroups each, and enough left over that ragged batches even out.
-constexpr int kTargetWorkgroups = 512;
+// Workgroups the decode grid should at least reach: one per compute unit.  Measured on
+// MI355X, four wavefronts per compute unit with three pages in flight each already saturate
+// HBM, and every further workgroup pays its own start-up (map and page-table look-ups, query
+// load) and merge, so the context is split no finer than needed to cover the 256 units.
+constexpr int kTargetWorkgroups = 256;
 constexpr int kMinPagesPerSplit = 4;   // one page per wavefront of the workgroup
 
 int check_desc(const kvs_desc* d)
