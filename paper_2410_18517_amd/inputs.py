@@ -9,7 +9,8 @@ The workloads stand in for the models the paper evaluates (Llama-2 7B/13B, Inter
 Sec. 4.1) and for its calibration set (30 sentences of equal length, Sec. 4.3): only the
 tensor shapes are taken from them; the contents are synthetic.
 """
-from dataclasses import dataclass, field
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass
 from typing import Optional
 
 import numpy as np
@@ -145,8 +146,20 @@ def calibration_kv(S, L, Hkv, T, d, *key, noise=1.0, dtype="bf16") -> torch.Tens
     a = torch.exp(torch.empty(L).uniform_(np.log(0.5), np.log(4.0), generator=g))
     beta = torch.randn(L, 2, d, generator=g)
     out = torch.empty(S, L, 2, Hkv * T * d, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
-    for s in range(S):
-        eps = torch.randn(L, 2, Hkv * T, d, generator=g) if noise else torch.zeros(L, 2, Hkv * T, d)
+
+    def one_sample(s):
+        if noise:
+            eps = torch.randn(L, 2, Hkv * T, d, generator=_gen(*key, 556, s))
+        else:
+            eps = torch.zeros(L, 2, Hkv * T, d)
         x = a.view(L, 1, 1, 1) * (beta.view(L, 2, 1, d) + noise * eps)
         out[s] = x.reshape(L, 2, Hkv * T * d).to(out.dtype)
+
+    parallel_map(one_sample, range(S))
     return out
+
+
+def parallel_map(fn, items, workers=16):
+    """Run independent draws on host threads (each has its own generator, so order is irrelevant)."""
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        return list(ex.map(fn, items))

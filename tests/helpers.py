@@ -50,7 +50,7 @@ class Case:
         return k, v
 
     def fill_layer(self, layer, T, keep_oracle_copy=True):
-        chunks = [self.kv_chunk(layer, b, T) for b in range(self.B)]
+        chunks = inputs.parallel_map(lambda b: self.kv_chunk(layer, b, T), range(self.B))
         k = torch.stack([c[0] for c in chunks])
         v = torch.stack([c[1] for c in chunks])
         st = self.kb.kvs_append_kv(self.store, layer, k.cuda(), v.cuda(),

@@ -1,0 +1,102 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times
+(full batch, full store geometry, default split policy, permuted page table).  The store is
+allocated at full size; only the layers that are sampled (recipients, their donors and layer 0)
+are filled, since a layer's kernel touches no other slot.  The oracle checks sampled sequences,
+all heads, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as orc
+from paper_2410_18517_amd import inputs
+from helpers import Case, rel_l2_rows, REL_L2_ATTENTION, REL_DISTANCE
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kb():
+    from paper_2410_18517_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.kvs_set_split_tokens(0)
+    return binding
+
+
+def _sample_layers(share):
+    recipients = [l for l in range(len(share)) if share[l] != l]
+    picked = [recipients[0], recipients[-1]] if recipients else []
+    layers = sorted(set([0] + picked + [int(share[r]) for r in picked]))
+    return layers, sorted(set(int(share[l]) for l in layers))
+
+
+def _sub(case, layer_arrays, b):
+    return [None if a is None else a[b:b + 1] for a in layer_arrays]
+
+
+@pytest.mark.parametrize("name", ["tiny", "llama2-7b", "llama2-13b", "llama3-8b-32k", "gqa48-ragged"])
+def test_decode_full_size_sampled(kb, name):
+    w = inputs.WORKLOADS[name]
+    share = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)
+    lens = inputs.make_seq_lens(w, 1)
+    layers, fill = _sample_layers(share)
+    case = Case(kb, w.L, w.Hq, w.Hkv, w.d, w.B, w.dtype, w.context, share, paged=True, seed=100,
+                fill_layers=fill, spare_blocks=0)
+    assert case.store.desc.n_slots == w.L - w.n_shared
+    tol = 1e-5 if w.dtype == "f32" else REL_L2_ATTENTION
+    seqs = sorted(set([int(np.argmax(lens)), int(np.argmin(lens)), w.B // 2]))
+    worst = 0.0
+    for layer in layers:
+        q = case.q(layer)
+        got = kb.kvs_decode_attention(case.store, layer, q.cuda(), lens).cpu().numpy()
+        assert np.isfinite(got).all()
+        for b in seqs:
+            want = orc.decode_attention(layer, share, _sub(case, case.K, b), _sub(case, case.V, b),
+                                        inputs.to_oracle_array(q[b:b + 1]), lens[b:b + 1])
+            err = rel_l2_rows(got[b:b + 1], want).max()
+            worst = max(worst, err)
+            assert err <= tol, (name, layer, b, err)
+    print(f"{name}: layers {layers}, sequences {seqs}, max rel L2 {worst:.2e}")
+
+
+def test_prefill_full_size_sampled(kb):
+    """Llama-2-13B shape: a 64-row causal chunk at the end of a 2048-token context; own-cache layers
+    append their 64 rows first, recipients read the donor's slot."""
+    w = inputs.WORKLOADS["llama2-13b"]
+    T_new = w.prefill_rows
+    share = inputs.make_share_map(w.L, w.n_shared, 1)
+    layers, fill = _sample_layers(share)
+    case = Case(kb, w.L, w.Hq, w.Hkv, w.d, w.B, w.dtype, w.context, share, paged=True, seed=200,
+                fill_layers=fill, fill_tokens=w.context - T_new, spare_blocks=0)
+    start = np.full(w.B, w.context - T_new, np.int32)
+    Ko = [None if x is None else np.concatenate([x, np.zeros((w.B, T_new, w.Hkv, w.d), x.dtype)], 1) for x in case.K]
+    Vo = [None if x is None else np.concatenate([x, np.zeros((w.B, T_new, w.Hkv, w.d), x.dtype)], 1) for x in case.V]
+    for layer in layers:                                  # layer order: donors before recipients
+        k_new = inputs.normal((w.B, T_new, w.Hkv, w.d), 200, layer, 50)
+        v_new = inputs.normal((w.B, T_new, w.Hkv, w.d), 200, layer, 51)
+        st = kb.kvs_append_kv(case.store, layer, k_new.cuda(), v_new.cuda(), start)
+        wrote = orc.append_kv(layer, share, Ko, Vo, inputs.to_oracle_array(k_new), inputs.to_oracle_array(v_new), start)
+        assert (st == kb.KVS_OK) == wrote
+        q = case.q(layer, rows=T_new)
+        got = kb.kvs_prefill_attention(case.store, layer, q.cuda(), start).cpu().numpy()
+        assert np.isfinite(got).all()
+        for b in (0, w.B - 1):
+            want = orc.shared_attention(layer, share, _sub(case, Ko, b), _sub(case, Vo, b),
+                                        inputs.to_oracle_array(q[b:b + 1]), start[b:b + 1])
+            assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, (layer, b)
+
+
+def test_distance_full_size(kb):
+    """Calibration of the 48-layer workload: 30 samples x 512 tokens x 8 kv heads x 128 (2.8 GiB)."""
+    S, L, Hkv, T, d = 30, 48, 8, 512, 128
+    kv = inputs.calibration_kv(S, L, Hkv, T, d, 300)
+    dK2, dV2, D = (t.cpu().numpy().astype(np.float64) for t in kb.kvs_layer_distance(kv.cuda()))
+    oK2, oV2, oD = orc.layer_distance(inputs.to_oracle_array(kv))
+    for got, want in ((dK2, oK2), (dV2, oV2), (D, oD)):
+        assert np.linalg.norm(got - want) <= REL_DISTANCE * np.linalg.norm(want)
+    off = ~np.eye(L, dtype=bool)
+    assert np.abs(D[off] / oD[off] - 1).max() <= 5 * REL_DISTANCE
+    assert np.array_equal(D, D.T) and np.all(np.diag(D) == 0)
+    from oracle import share_map as osm
+    got = kb.kvs_build_share_map(D.astype(np.float32), 14)
+    want = osm.build_share_map(D.astype(np.float32), L, 14)
+    assert (got[0], got[1].tolist(), got[2].tolist(), got[3], got[4]) == want and got[3] == 34
