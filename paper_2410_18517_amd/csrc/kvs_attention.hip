@@ -198,7 +198,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a)
 
 // ------------------------------------------------------------------ bf16 store, MFMA
 //
-// Work split: grid = (n_splits * n_col_groups, Hkv, B).  A workgroup owns one kv head of one
+// Work split: grid = (Hkv, B, n_splits * n_col_groups).  A workgroup owns one kv head of one
 // sequence, NT tiles of 16 query columns (a column is a (query row, head-in-group) pair; a
 // decode step has one row, so one tile holds the whole GQA group) and a contiguous range of
 // pages.  Its four wavefronts take pages round-robin, each streaming its pages from HBM
@@ -264,43 +264,61 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int quad = lane >> 4, col = lane & 15;
-    const int split = blockIdx.x % a.n_splits;
-    const int cgrp = blockIdx.x / a.n_splits;
-    const int g = blockIdx.y, b = blockIdx.z;
+    // Workgroup ids go round-robin over the chip's eight XCDs, so the fastest-varying index
+    // must be one whose every value carries work: the kv head.  A split index there would
+    // park whole XCDs on the empty splits of short sequences.
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int split = NT == 1 ? (int)blockIdx.z : (int)blockIdx.z % a.n_splits;   // one decode row: one column group
+    const int cgrp = NT == 1 ? 0 : (int)blockIdx.z / a.n_splits;
     const int group = st.Hq / st.Hkv;
     const int ncols = a.T_new * group;
     const int cap = st.max_blocks_per_seq * kPageTokens;
+    const int page_lo = split * a.pages_per_split;
+    const int my_first = page_lo + wave;
 
-    // keys visible to query row 0; row r sees n0 + r
-    int n0 = a.lens[b] + a.lens_bias;
-    n0 = n0 < 0 ? 0 : n0;
-    if (n0 > cap - (a.T_new - 1)) n0 = cap - (a.T_new - 1);
+    // Start-up look-ups in one round trip: a single vector load in which lane 0 fetches the
+    // sequence length, lane 1 the layer's donor, lanes 2..7 the page-table entries of the first
+    // pages (index clamped into the table, so they can be fetched before the length says how
+    // many are used) and lanes 8..63 the slots of layers 0..55; the values are then read out of
+    // the lanes.  Only a donor beyond layer 55 costs a second, dependent look-up.
+    static_assert(kPrefetch <= 6, "lanes 2..7 carry the first page-table entries");
+    int first_page[kPrefetch];
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j) {
+        const int pg = my_first + j * kWaves;
+        first_page[j] = pg < st.max_blocks_per_seq ? pg : st.max_blocks_per_seq - 1;
+    }
+    const int32_t* look = nullptr;
+    if (lane == 0) look = a.lens + b;
+    else if (lane == 1) look = st.share_map + st.layer;
+    else if (lane < 8) {
+        int pg = first_page[0];
+#pragma unroll
+        for (int j = 1; j < kPrefetch; ++j) pg = lane - 2 == j ? first_page[j] : pg;
+        if (st.block_table && lane - 2 < kPrefetch) look = st.block_table + (size_t)b * st.max_blocks_per_seq + pg;
+    } else if (lane - 8 < st.L) look = st.slot_of_layer + (lane - 8);
+    const int looked = look ? *look : 0;
+    const int len_raw = __builtin_amdgcn_readlane(looked, 0);
+    const int donor_raw = __builtin_amdgcn_readlane(looked, 1);
+    int first_blk[kPrefetch];
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j) {
+        int blk = st.block_table ? __builtin_amdgcn_readlane(looked, 2 + j) : b * st.max_blocks_per_seq + first_page[j];
+        first_blk[j] = blk < 0 ? 0 : (blk >= st.num_blocks ? st.num_blocks - 1 : blk);
+    }
 
-    // columns of this lane, one per tile
-    int n_col[NT];
+    // columns of this lane, one per tile, and their query fragments (B operand of the score MFMA)
     size_t q_off[NT];
     bool col_ok[NT];
+    int col_row[NT];
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) {
         const int cidx = (cgrp * NT + ct) * 16 + col;
         col_ok[ct] = cidx < ncols;
-        const int r = col_ok[ct] ? cidx / group : 0;
+        col_row[ct] = col_ok[ct] ? cidx / group : 0;
         const int hc = col_ok[ct] ? cidx % group : 0;
-        n_col[ct] = n0 + r;
-        q_off[ct] = (((size_t)b * a.T_new + r) * st.Hq + g * group + hc) * D;
+        q_off[ct] = (((size_t)b * a.T_new + col_row[ct]) * st.Hq + g * group + hc) * D;
     }
-    // rows covered by the workgroup bound the pages it needs
-    const int c_lo = cgrp * NT * 16;
-    int c_hi = c_lo + NT * 16 - 1;
-    if (c_hi > ncols - 1) c_hi = ncols - 1;
-    const int n_min = n0 + c_lo / group;          // fewest keys any of its rows sees
-    const int n_max = n0 + c_hi / group;          // most keys, = tokens certainly stored
-    const int pages_total = (n_max + kPageTokens - 1) / kPageTokens;
-    const int page_lo = split * a.pages_per_split;
-    int page_hi = page_lo + a.pages_per_split;
-    if (page_hi > pages_total) page_hi = pages_total;
-
-    // query fragments: B operand of the score MFMA
     bf16x8 qf[NT][KS];
     const unsigned short* qbase = static_cast<const unsigned short*>(a.q);
 #pragma unroll
@@ -312,6 +330,35 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             qf[ct][s] = __builtin_bit_cast(bf16x8, w);
         }
 
+    // the strategy's substitution: this layer reads the slot of its donor (itself if none)
+    const int donor = donor_raw < 0 ? 0 : (donor_raw >= st.L ? st.L - 1 : donor_raw);
+    const int slot_raw = donor < 56 ? __builtin_amdgcn_readlane(looked, 8 + donor) : st.slot_of_layer[donor];
+    const int slot = slot_raw < 0 ? 0 : (slot_raw >= st.n_slots ? st.n_slots - 1 : slot_raw);
+
+    // keys visible to query row 0; row r sees n0 + r
+    int n0 = len_raw + a.lens_bias;
+    n0 = n0 < 0 ? 0 : n0;
+    if (n0 > cap - (a.T_new - 1)) n0 = cap - (a.T_new - 1);
+    int n_col[NT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) n_col[ct] = n0 + col_row[ct];
+    // rows covered by the workgroup bound the pages it needs
+    const int c_lo = cgrp * NT * 16;
+    int c_hi = c_lo + NT * 16 - 1;
+    if (c_hi > ncols - 1) c_hi = ncols - 1;
+    const int n_min = n0 + c_lo / group;          // fewest keys any of its rows sees
+    const int n_max = n0 + c_hi / group;          // most keys, = tokens certainly stored
+    const int pages_total = (n_max + kPageTokens - 1) / kPageTokens;
+    int page_hi = page_lo + a.pages_per_split;
+    if (page_hi > pages_total) page_hi = pages_total;
+    const int my_pages = my_first < page_hi ? (page_hi - my_first + kWaves - 1) / kWaves : 0;
+
+    const unsigned short* pool = static_cast<const unsigned short*>(st.pool);
+    PageRegs<D> buf[kPrefetch];
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j)
+        if (j < my_pages) load_page<D>(buf[j], pool, page_offset(st, slot, first_blk[j], g), lane);
+
     const float scale_log2 = 1.44269504088896340736f * (D == 128 ? 0.08838834764831845f : 0.125f);
     float m[NT], l[NT];
     floatx4 o[NT][DT];
@@ -322,17 +369,6 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 #pragma unroll
         for (int c = 0; c < DT; ++c) o[ct][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
-
-    const int slot = resolve_slot(st);
-    const unsigned short* pool = static_cast<const unsigned short*>(st.pool);
-    const int my_first = page_lo + wave;
-    const int my_pages = my_first < page_hi ? (page_hi - my_first + kWaves - 1) / kWaves : 0;
-
-    PageRegs<D> buf[kPrefetch];
-#pragma unroll
-    for (int j = 0; j < kPrefetch; ++j)
-        if (j < my_pages)
-            load_page<D>(buf[j], pool, page_offset(st, slot, safe_block_of(st, b, my_first + j * kWaves), g), lane);
 
     for (int k0 = 0; k0 < my_pages; k0 += kPrefetch) {
 #pragma unroll
@@ -463,7 +499,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     if (threadIdx.x == 0) {
-        const int n_col_groups = gridDim.x / a.n_splits;
+        const int n_col_groups = gridDim.z / a.n_splits;
         int* counter = a.counters + ((size_t)b * st.Hkv + g) * n_col_groups + cgrp;
         const int arrived = atomicAdd(counter, 1);
         s_is_last = arrived == a.n_splits - 1;
@@ -506,11 +542,11 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
 {
     const int group = a.st.Hq / a.st.Hkv;
     if (a.T_new == 1) {
-        dim3 grid(a.n_splits, a.st.Hkv, a.B);
+        dim3 grid(a.st.Hkv, a.B, a.n_splits);
         hipLaunchKernelGGL((attn_bf16_kernel<D, 1>), grid, dim3(kThreads), 0, s, a);
     } else {
         const int cgroups = (a.T_new * group + 63) / 64;
-        dim3 grid(a.n_splits * cgroups, a.st.Hkv, a.B);
+        dim3 grid(a.st.Hkv, a.B, a.n_splits * cgroups);
         hipLaunchKernelGGL((attn_bf16_kernel<D, 4>), grid, dim3(kThreads), 0, s, a);
     }
     if (hipError_t e = hipGetLastError()) return (int)e;

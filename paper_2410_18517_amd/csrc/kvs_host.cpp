@@ -324,8 +324,9 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
         return fail(KVS_ERR_CAPACITY, "T_new=%d exceeds the per-sequence capacity", T_new);
     if (!store->block_table && (long)B * d->max_blocks_per_seq > d->num_blocks)
         return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
-    if (B > 65535 || d->Hkv > 65535) return fail(KVS_ERR_CAPACITY, "B and Hkv are limited to 65535");
     const Split s = choose_split(d, B, T_new);
+    if (B > 65535 || (long)s.n_splits * s.n_col_groups > 65535)
+        return fail(KVS_ERR_CAPACITY, "launch too large: B and splits x column groups are limited to 65535");
     const size_t need = counter_bytes(d, B, s) + partial_floats(d, B, T_new, s) * sizeof(float);
     if (!workspace || workspace_bytes < need)
         return fail(KVS_ERR_INVALID_ARG, "workspace too small: need %zu bytes, got %zu", need, workspace_bytes);
