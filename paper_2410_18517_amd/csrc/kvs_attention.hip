@@ -15,6 +15,7 @@ constexpr int kPageTokens = 16;
 constexpr int kWaves = 4;              // wavefronts per workgroup of the bf16 kernel
 constexpr int kThreads = kWaves * 64;
 constexpr int kPrefetch = 3;           // pages each wavefront keeps in flight
+constexpr float kRefSlack = 8.f;       // log2 units a score may exceed the softmax reference by
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
@@ -255,6 +256,25 @@ __device__ __forceinline__ floatx2 fetch_pair(const float* p)
     return __builtin_bit_cast(floatx2, w);
 }
 
+// Reductions over the four lanes l, l^16, l^32, l^48 that hold one query column, with the
+// gfx950 lane-swap instructions: permlane16_swap(x, x) returns the pair (rows 0,0,2,2 of x,
+// rows 1,1,3,3 of x) for 16-lane rows, permlane32_swap the same for 32-lane halves, so two
+// swaps and two combines replace two round trips through the LDS crossbar.
+__device__ __forceinline__ float column_max(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float column_sum(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 template <int D, int NT>
 __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 {
@@ -392,45 +412,58 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             }
             const bool need_mask = tok0 + kPageTokens > n_min;
 
+            // Three phases over all column tiles, so that independent MFMAs and independent
+            // softmax updates sit next to each other and can overlap within the wavefront.
+            floatx4 sc[NT];
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) sc[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct)
+                    sc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[s]),
+                                                                     qf[ct][s], sc[ct], 0, 0, 0);
+            shortx4 pf[NT];
 #pragma unroll
             for (int ct = 0; ct < NT; ++ct) {
-                floatx4 sc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < KS; ++s)
-                    sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[s]),
-                                                                 qf[ct][s], sc, 0, 0, 0);
                 float z[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) z[i] = sc[i] * scale_log2;
+                for (int i = 0; i < 4; ++i) z[i] = sc[ct][i] * scale_log2;
                 if (need_mask) {
                     const int t = tok0 + quad * 4;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) z[i] = (t + i < n_col[ct]) ? z[i] : -INFINITY;
                 }
-                float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m[ct], mx);
+                const float mx = column_max(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])));
+                // m is the reference of the exponentials, not necessarily the running maximum:
+                // softmax is shift invariant, so the reference only moves (and o, l are only
+                // rescaled) when a score exceeds it by more than kRefSlack; until then weights
+                // may reach 2^kRefSlack, which fp32 sums and bf16 operands hold without loss.
+                const bool up = mx > m[ct] + kRefSlack;              // false while everything is masked
+                const float m_new = up ? mx : m[ct];
                 const float m_use = m_new == -INFINITY ? 0.f : m_new;   // column sees nothing yet
-                const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_use);
                 float p[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_use);
-                l[ct] = l[ct] * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
-                if (!__all(m_new == m[ct])) {
+                if (__any(up)) {
+                    const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_use);   // 1 in lanes that keep their reference
+                    l[ct] *= alpha;
 #pragma unroll
                     for (int c = 0; c < DT; ++c) o[ct][c] *= alpha;
+                    m[ct] = m_new;
                 }
-                m[ct] = m_new;
+                l[ct] += (p[0] + p[1]) + (p[2] + p[3]);
                 const uint2 pw = make_uint2(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]));
-                const shortx4 pf = __builtin_bit_cast(shortx4, pw);
+                pf[ct] = __builtin_bit_cast(shortx4, pw);
+            }
 #pragma unroll
-                for (int c = 0; c < DT; ++c) {
-                    const uint4 vv = cur.v[c >> 1];
-                    const uint2 half = (c & 1) ? make_uint2(vv.z, vv.w) : make_uint2(vv.x, vv.y);
-                    o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, half), pf,
+            for (int c = 0; c < DT; ++c) {
+                const uint4 vv = cur.v[c >> 1];
+                const uint2 half = (c & 1) ? make_uint2(vv.z, vv.w) : make_uint2(vv.x, vv.y);
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct)
+                    o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, half), pf[ct],
                                                                          o[ct][c], 0, 0, 0);
-                }
             }
             if (k + kPrefetch < my_pages)
                 load_page<D>(buf[j], pool,
@@ -444,9 +477,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     __shared__ float lds_l[kWaves][16];
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) {
-        float lsum = l[ct];
-        lsum += __shfl_xor(lsum, 16);
-        lsum += __shfl_xor(lsum, 32);
+        const float lsum = column_sum(l[ct]);
         if (ct > 0) __syncthreads();
         if (quad == 0) {
             lds_m[wave][col] = m[ct];

@@ -107,6 +107,34 @@ def test_many_splits_merge_is_exact_and_repeatable(kb):
         kb.kvs_set_split_tokens(0)
 
 
+@pytest.mark.parametrize("gain", [0.05, 4.0, 24.0])
+def test_bf16_flat_and_peaked_softmax(kb, gain):
+    """Scores from nearly constant to widely spread (the running reference of the exponentials has
+    to move many times, by small and by large steps), keys sorted so that the maximum keeps rising."""
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, 2, 8, 2, 128, 3, "bf16", 1500, share, seed=23)
+    lens = np.array([1500, 700, 33], np.int32)
+    q = (case.q(1).float() * gain).to(torch.bfloat16)
+    for split in (0, 256):
+        kb.kvs_set_split_tokens(split)
+        got = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens).cpu().numpy()
+        want = orc.decode_attention(1, share, case.K, case.V, inputs.to_oracle_array(q), lens)
+        assert np.isfinite(got).all()
+        assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION, (gain, split)
+    kb.kvs_set_split_tokens(0)
+    # rising scores: key j is a growing multiple of q's direction for head 0 of sequence 0
+    k_up = torch.from_numpy(case.K[0].view(np.int16)).view(torch.bfloat16).clone()
+    ramp = torch.linspace(-1.0, 1.0, 1500).view(1, 1500, 1, 1)
+    k_up = (k_up.float() * 0.1 + ramp * q[:1, :1].float().reshape(1, 1, 1, 128)).to(torch.bfloat16)
+    v = torch.from_numpy(case.V[0].view(np.int16)).view(torch.bfloat16)
+    kb.kvs_append_kv(case.store, 0, k_up.expand(3, -1, 2, -1).contiguous().cuda(), v.contiguous().cuda(),
+                     np.zeros(3, np.int32))
+    Ko = [inputs.to_oracle_array(k_up.expand(3, -1, 2, -1).contiguous()), None]
+    got = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens).cpu().numpy()
+    want = orc.decode_attention(1, share, Ko, case.V, inputs.to_oracle_array(q), lens)
+    assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
+
+
 def test_bf16_unwritten_tail_cannot_leak(kb):
     """Rows past seq_len hold NaN bit patterns: they must not reach the output."""
     share = np.array([0, 0], np.int32)
