@@ -49,6 +49,90 @@ def recorded_traffic(workload):
     return int(rec["traffic_bytes_per_launch"])
 
 
+def _event_time_us(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    pairs = []
+    for _ in range(steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    return float(np.mean([a.elapsed_time(b) for a, b in pairs])) * 1e3
+
+
+def bench_prefill(args, torch, kb, inputs, dev):
+    """Causal prefill chunk of the Llama-2-13B shape: 64 new rows per sequence behind a 1984-token
+    prefix; a step = append of the 64 rows + attention over the 2048 keys, for one layer."""
+    w = inputs.WORKLOADS["llama2-13b"]
+    T, n_layers = w.prefill_rows, 3                       # rotate over three layers' slots
+    mb = w.max_blocks_per_seq
+    table = inputs.make_block_table(w.B, mb, w.B * mb, 1)
+    store = kb.KVStore(np.arange(n_layers, dtype=np.int32), w.Hq, w.Hkv, w.d, "bf16", w.B * mb, mb, block_table=table)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_BASE)
+    zeros = torch.zeros(w.B, dtype=torch.int32, device=dev)
+    for l in range(n_layers):
+        k = torch.randn((w.B, w.context, w.Hkv, w.d), device=dev, generator=gen).bfloat16()
+        v = torch.randn((w.B, w.context, w.Hkv, w.d), device=dev, generator=gen).bfloat16()
+        kb.kvs_append_kv(store, l, k, v, zeros)
+    q = torch.randn((w.B, T, w.Hq, w.d), device=dev, generator=gen).bfloat16()
+    k_new = torch.randn((w.B, T, w.Hkv, w.d), device=dev, generator=gen).bfloat16()
+    start = torch.full((w.B,), w.context - T, dtype=torch.int32, device=dev)
+    out = torch.empty((w.B, T, w.Hq, w.d), dtype=torch.float32, device=dev)
+    ws = store.workspace(w.B, T)
+    it = [0]
+
+    def attn():
+        kb.kvs_prefill_attention(store, it[0] % n_layers, q, start, out=out, workspace=ws)
+        it[0] += 1
+
+    def append():
+        kb.kvs_append_kv(store, it[0] % n_layers, k_new, k_new, start)
+        it[0] += 1
+
+    attn_us = _event_time_us(torch, attn, args.steps, args.warmup)
+    append_us = _event_time_us(torch, append, args.steps, args.warmup)
+    kv_bytes = w.B * w.context * w.Hkv * w.d * 2 * 2 + w.B * T * w.Hq * w.d * (2 + 4)
+    achieved = kv_bytes / attn_us / 1e3
+    print(json.dumps({
+        "metric": "causal prefill chunk attention, rows/s", "value": round(w.B * T / (attn_us * 1e-6), 1),
+        "unit": "query rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(attn_us * 1e-3, 4), "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama2-13b prefill chunk", "batch": w.B, "rows": T, "prefix": w.context - T,
+                   "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d},
+        "append_us": round(append_us, 2),
+        "roofline": {"bound": "hbm", "kernel": "attn_bf16_kernel<128,4>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": None, "launch_us": round(attn_us, 2), "algorithmic_bytes": kv_bytes}}))
+
+
+def bench_distance(args, torch, kb, inputs, dev):
+    """Calibration of the 48-layer workload: 30 samples x 512 tokens x 8 kv heads x 128, bf16."""
+    S, L, N = 30, 48, 8 * 512 * 128
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_BASE)
+    kv = torch.empty((S, L, 2, N), device=dev, dtype=torch.bfloat16)
+    for s_ in range(S):
+        kv[s_] = torch.randn((L, 2, N), device=dev, generator=gen).bfloat16()
+    ws = torch.empty(kb.lib().kvs_distance_workspace_bytes(L), dtype=torch.uint8, device=dev)
+    us = _event_time_us(torch, lambda: kb.kvs_layer_distance(kv, workspace=ws), args.steps, args.warmup)
+    nbytes = kv.numel() * 2 + 3 * L * L * 4
+    achieved = nbytes / us / 1e3
+    print(json.dumps({
+        "metric": "layer-distance matrix, calibration bytes/s", "value": round(achieved, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us * 1e-3, 4),
+        "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "calibration 30 x 48 layers x (8 x 512 x 128)", "samples": S, "layers": L, "N": N},
+        "roofline": {"bound": "hbm", "kernel": "distance_partial_kernel<bf16> + distance_final_kernel",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "launch_us": round(us, 2),
+                     "algorithmic_bytes": nbytes}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +141,10 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--mode", choices=["decode", "prefill", "distance"], default="decode",
+                    help="decode (default): the whole decode step, the headline metric.  prefill: the 64-row "
+                         "causal chunk of the llama2-13b workload.  distance: the 48-layer calibration matrix. "
+                         "The last two time the other kernels of the path, one JSON line each.")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (torch) so that a counter trace of this "
                          "command contains a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -70,9 +158,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    w = inputs.WORKLOADS[args.workload]
     if args.split_tokens:
         kb.kvs_set_split_tokens(args.split_tokens)
+    if args.mode == "prefill":
+        return bench_prefill(args, torch, kb, inputs, dev)
+    if args.mode == "distance":
+        return bench_distance(args, torch, kb, inputs, dev)
+    w = inputs.WORKLOADS[args.workload]
 
     share = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)
     seq_lens = inputs.make_seq_lens(w, 1)
