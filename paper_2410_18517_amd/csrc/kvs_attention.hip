@@ -14,7 +14,6 @@ namespace {
 constexpr int kPageTokens = 16;
 constexpr int kWaves = 4;              // wavefronts per workgroup of the bf16 kernel
 constexpr int kThreads = kWaves * 64;
-constexpr int kPrefetch = 3;           // pages each wavefront keeps in flight
 constexpr float kRefSlack = 8.f;       // log2 units a score may exceed the softmax reference by
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -210,10 +209,12 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a)
 // folds its splits into the output.
 //
 // MFMA roles.  Scores: S[token][column] = K_page(16 x D) . Q^T(D x 16) with
-// v_mfma_f32_16x16x32_bf16; lane l holds the scores of column l%16 for tokens 4*(l/16)..+3,
-// which is exactly the B-operand layout of v_mfma_f32_16x16x16_bf16, so the probabilities feed
-// O^T[channel][column] += V^T(16 x 16 tokens) . P^T(16 tokens x 16 columns) without leaving
-// their registers.
+// v_mfma_f32_16x16x32_bf16; lane l holds the scores of column l%16 for tokens 4*(l/16)..+3 of
+// the page.  Two pages give a lane eight probabilities, which is exactly a B operand of the
+// same instruction (contraction over 32 tokens: slots 0-3 from the first page, 4-7 from the
+// second), and the V pages are stored so that a lane's registers are the matching A operand:
+// O^T[channel][column] += V^T(16 x 32 tokens) . P^T(32 tokens x 16 columns) without any data
+// leaving its registers.
 template <int D>
 struct PageRegs {
     uint4 k[D / 32];
@@ -230,6 +231,19 @@ __device__ __forceinline__ void load_page(PageRegs<D>& r, const unsigned short* 
     for (int s = 0; s < D / 32; ++s) r.k[s] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(kp + s * 64));
 #pragma unroll
     for (int s = 0; s < D / 32; ++s) r.v[s] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(vp + s * 64));
+}
+
+// Zero the values of tokens `first`.. of this lane's four (first <= 0 clears all four): the
+// lane holds tokens 4*quad..4*quad+3 of the page, two per 32-bit word, for two channel tiles.
+template <int D>
+__device__ __forceinline__ void clear_values_from(PageRegs<D>& r, int first)
+{
+    const unsigned m01 = (0 < first ? 0x0000ffffu : 0u) | (1 < first ? 0xffff0000u : 0u);
+    const unsigned m23 = (2 < first ? 0x0000ffffu : 0u) | (3 < first ? 0xffff0000u : 0u);
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+        r.v[s].x &= m01; r.v[s].y &= m23; r.v[s].z &= m01; r.v[s].w &= m23;
+    }
 }
 
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
@@ -275,9 +289,10 @@ __device__ __forceinline__ float column_sum(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-template <int D, int NT>
+template <int D, int NT, int kPrefetch>
 __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 {
+    // kPrefetch: pages each wavefront keeps in flight (consumed in pairs)
     constexpr int KS = D / 32;   // k-steps of the score MFMA = 1-KiB chunks per page
     constexpr int DT = D / 16;   // 16-channel tiles of the output
     const StoreView& st = a.st;
@@ -372,6 +387,10 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     int page_hi = page_lo + a.pages_per_split;
     if (page_hi > pages_total) page_hi = pages_total;
     const int my_pages = my_first < page_hi ? (page_hi - my_first + kWaves - 1) / kWaves : 0;
+    // Splits that hold keys for this (sequence, column group).  Workgroups past them leave at
+    // once; if there is at most one, split 0 writes the output itself and no state is published.
+    const int live_splits = (pages_total + a.pages_per_split - 1) / a.pages_per_split;
+    if (split > 0 && split >= live_splits) return;
 
     const unsigned short* pool = static_cast<const unsigned short*>(st.pool);
     PageRegs<D> buf[kPrefetch];
@@ -390,51 +409,67 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
         for (int c = 0; c < DT; ++c) o[ct][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    for (int k0 = 0; k0 < my_pages; k0 += kPrefetch) {
+    // Pages are consumed two at a time: 32 tokens fill the contraction depth of the 16x16x32
+    // MFMA for P.V as well, two independent score chains overlap, and one softmax update
+    // (one column maximum, one reference test) serves both pages.  A wavefront with an odd
+    // page count pairs its last page with an absent one whose scores are masked and whose
+    // operand registers are zero.
+    static_assert(kPrefetch % 2 == 0, "buffers are used in pairs");
+    const int my_pairs = (my_pages + 1) / 2;
+    for (int p0 = 0; p0 < my_pairs; p0 += kPrefetch / 2) {
 #pragma unroll
-        for (int j = 0; j < kPrefetch; ++j) {
-            const int k = k0 + j;
-            if (k >= my_pages) break;
-            const int page = my_first + k * kWaves;
-            const int tok0 = page * kPageTokens;
-            PageRegs<D>& cur = buf[j];
+        for (int jj = 0; jj < kPrefetch / 2; ++jj) {
+            const int pr = p0 + jj;
+            if (pr >= my_pairs) break;
+            PageRegs<D>& pa = buf[2 * jj];
+            PageRegs<D>& pb = buf[2 * jj + 1];
+            const int ka = 2 * pr, kb = ka + 1;
+            const bool have_b = kb < my_pages;
+            const int page_a = my_first + ka * kWaves, page_b = my_first + kb * kWaves;
+            const int tok_a = page_a * kPageTokens, tok_b = page_b * kPageTokens;
 
-            if (tok0 + kPageTokens > n_max) {
-                // tokens past the stored length hold whatever the allocation held: clear their
-                // values so a zero probability cannot meet a NaN
-                const int t = tok0 + quad * 4;
-                const unsigned m01 = (t + 0 < n_max ? 0x0000ffffu : 0u) | (t + 1 < n_max ? 0xffff0000u : 0u);
-                const unsigned m23 = (t + 2 < n_max ? 0x0000ffffu : 0u) | (t + 3 < n_max ? 0xffff0000u : 0u);
+            // tokens past the stored length hold whatever the allocation held: clear their
+            // values so a zero probability cannot meet a NaN
+            if (tok_a + kPageTokens > n_max) clear_values_from<D>(pa, n_max - tok_a - quad * 4);
+            if (!have_b) {
 #pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    cur.v[s].x &= m01; cur.v[s].y &= m23; cur.v[s].z &= m01; cur.v[s].w &= m23;
-                }
+                for (int s = 0; s < KS; ++s) pb.k[s] = pb.v[s] = make_uint4(0, 0, 0, 0);
+            } else if (tok_b + kPageTokens > n_max) {
+                clear_values_from<D>(pb, n_max - tok_b - quad * 4);
             }
-            const bool need_mask = tok0 + kPageTokens > n_min;
+            const bool need_mask = !have_b || tok_b + kPageTokens > n_min || tok_a + kPageTokens > n_min;
 
-            // Three phases over all column tiles, so that independent MFMAs and independent
-            // softmax updates sit next to each other and can overlap within the wavefront.
-            floatx4 sc[NT];
+            floatx4 sa[NT], sb[NT];
 #pragma unroll
-            for (int ct = 0; ct < NT; ++ct) sc[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int ct = 0; ct < NT; ++ct) sa[ct] = sb[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < KS; ++s)
 #pragma unroll
-                for (int ct = 0; ct < NT; ++ct)
-                    sc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[s]),
-                                                                     qf[ct][s], sc[ct], 0, 0, 0);
-            shortx4 pf[NT];
+                for (int ct = 0; ct < NT; ++ct) {
+                    sa[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa.k[s]), qf[ct][s],
+                                                                     sa[ct], 0, 0, 0);
+                    sb[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pb.k[s]), qf[ct][s],
+                                                                     sb[ct], 0, 0, 0);
+                }
+            bf16x8 pf[NT];
 #pragma unroll
             for (int ct = 0; ct < NT; ++ct) {
-                float z[4];
+                float z[8];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) z[i] = sc[ct][i] * scale_log2;
-                if (need_mask) {
-                    const int t = tok0 + quad * 4;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) z[i] = (t + i < n_col[ct]) ? z[i] : -INFINITY;
+                for (int i = 0; i < 4; ++i) {
+                    z[i] = sa[ct][i] * scale_log2;
+                    z[4 + i] = sb[ct][i] * scale_log2;
                 }
-                const float mx = column_max(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])));
+                if (need_mask) {
+                    const int ta = tok_a + quad * 4, tb = tok_b + quad * 4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        z[i] = (ta + i < n_col[ct]) ? z[i] : -INFINITY;
+                        z[4 + i] = (have_b && tb + i < n_col[ct]) ? z[4 + i] : -INFINITY;
+                    }
+                }
+                const float mx = column_max(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
+                                                  fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
                 // m is the reference of the exponentials, not necessarily the running maximum:
                 // softmax is shift invariant, so the reference only moves (and o, l are only
                 // rescaled) when a score exceeds it by more than kRefSlack; until then weights
@@ -442,9 +477,9 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
                 const bool up = mx > m[ct] + kRefSlack;              // false while everything is masked
                 const float m_new = up ? mx : m[ct];
                 const float m_use = m_new == -INFINITY ? 0.f : m_new;   // column sees nothing yet
-                float p[4];
+                float p[8];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_use);
+                for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_use);
                 if (__any(up)) {
                     const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_use);   // 1 in lanes that keep their reference
                     l[ct] *= alpha;
@@ -452,22 +487,25 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
                     for (int c = 0; c < DT; ++c) o[ct][c] *= alpha;
                     m[ct] = m_new;
                 }
-                l[ct] += (p[0] + p[1]) + (p[2] + p[3]);
-                const uint2 pw = make_uint2(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]));
-                pf[ct] = __builtin_bit_cast(shortx4, pw);
+                l[ct] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+                const uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
+                                            pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+                pf[ct] = __builtin_bit_cast(bf16x8, pw);
             }
 #pragma unroll
             for (int c = 0; c < DT; ++c) {
-                const uint4 vv = cur.v[c >> 1];
-                const uint2 half = (c & 1) ? make_uint2(vv.z, vv.w) : make_uint2(vv.x, vv.y);
+                const uint4 va = pa.v[c >> 1], vb = pb.v[c >> 1];
+                // contraction slots 0-3: tokens 4*quad.. of the first page, 4-7: of the second
+                const uint4 vcat = (c & 1) ? make_uint4(va.z, va.w, vb.z, vb.w) : make_uint4(va.x, va.y, vb.x, vb.y);
 #pragma unroll
                 for (int ct = 0; ct < NT; ++ct)
-                    o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, half), pf[ct],
-                                                                         o[ct][c], 0, 0, 0);
+                    o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vcat), pf[ct],
+                                                                       o[ct][c], 0, 0, 0);
             }
-            if (k + kPrefetch < my_pages)
-                load_page<D>(buf[j], pool,
-                             page_offset(st, slot, safe_block_of(st, b, page + kPrefetch * kWaves), g), lane);
+            if (ka + kPrefetch < my_pages)
+                load_page<D>(pa, pool, page_offset(st, slot, safe_block_of(st, b, page_a + kPrefetch * kWaves), g), lane);
+            if (kb + kPrefetch < my_pages)
+                load_page<D>(pb, pool, page_offset(st, slot, safe_block_of(st, b, page_b + kPrefetch * kWaves), g), lane);
         }
     }
 
@@ -506,7 +544,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             }
             const int r = cidx / group, hc = cidx % group;
             const size_t row = ((size_t)b * a.T_new + r) * st.Hq + g * group + hc;
-            if (a.n_splits == 1) {
+            if (live_splits <= 1) {
                 const float inv = lt > 0.f ? 1.f / lt : 0.f;
                 *reinterpret_cast<floatx4*>(a.out + row * D + d4) = acc * inv;
             } else {
@@ -518,11 +556,11 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             }
         }
     }
-    if (a.n_splits == 1) return;
+    if (live_splits <= 1) return;
 
     // The workgroup that arrives last at this (sequence, kv head, column group) merges the
     // splits.  Nobody waits: each workgroup publishes its partial state, bumps the counter
-    // and leaves; the one that reads n_splits - 1 finds every other state already published.
+    // and leaves; the one that reads (live splits - 1) finds every other state already published.
     __shared__ int s_is_last;
     // vmcnt(0): every device-scope store this wavefront issued has been acknowledged.  A
     // workgroup-scope fence would not wait for that (the compute unit orders its own accesses).
@@ -533,7 +571,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
         const int n_col_groups = gridDim.z / a.n_splits;
         int* counter = a.counters + ((size_t)b * st.Hkv + g) * n_col_groups + cgrp;
         const int arrived = atomicAdd(counter, 1);
-        s_is_last = arrived == a.n_splits - 1;
+        s_is_last = arrived == live_splits - 1;
         if (s_is_last) atomicExch(counter, 0);          // leave the counter ready for the next call
     }
     __syncthreads();
@@ -549,12 +587,12 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
         const float* part = a.partials + row * a.n_splits * (size_t)(D + 2);
         float M = -INFINITY;
 #pragma unroll 8
-        for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, fetch_pair(part + s * (D + 2) + D)[0]);
+        for (int s = 0; s < live_splits; ++s) M = fmaxf(M, fetch_pair(part + s * (D + 2) + D)[0]);
         const float M_use = M == -INFINITY ? 0.f : M;
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
         float lt = 0.f;
 #pragma unroll 4
-        for (int s = 0; s < a.n_splits; ++s) {
+        for (int s = 0; s < live_splits; ++s) {
             const float* ps = part + s * (D + 2);
             const floatx2 ml = fetch_pair(ps + D);
             const floatx2 lo = fetch_pair(ps + d4);
@@ -574,11 +612,11 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
     const int group = a.st.Hq / a.st.Hkv;
     if (a.T_new == 1) {
         dim3 grid(a.st.Hkv, a.B, a.n_splits);
-        hipLaunchKernelGGL((attn_bf16_kernel<D, 1>), grid, dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, 1, 4>), grid, dim3(kThreads), 0, s, a);
     } else {
         const int cgroups = (a.T_new * group + 63) / 64;
         dim3 grid(a.st.Hkv, a.B, a.n_splits * cgroups);
-        hipLaunchKernelGGL((attn_bf16_kernel<D, 4>), grid, dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, 4, 2>), grid, dim3(kThreads), 0, s, a);
     }
     if (hipError_t e = hipGetLastError()) return (int)e;
     return 0;
