@@ -193,6 +193,26 @@ int kvs_layer_distance(const void* kv_samples, int S, int L, size_t N, int dtype
 
 size_t kvs_distance_workspace_bytes(int L);
 
+/* ---------------------------------------------------------------- similarity test */
+
+/*
+ * Representation similarity of Algorithm 1 ("Avg_Cos_Sim") and Sec. 3.1.2: hidden_shared and
+ * hidden_original are the last-layer hidden states of the model with the candidate strategy
+ * and of the original model on the calibration set, device [S][N] of `dtype` (S sentences of
+ * equal length, N = tokens x hidden size, flattened).  *similarity (device, one float):
+ *   mode 0: cosine similarity of the two sentence-averaged vectors (the text of Sec. 3.1.2:
+ *           "average these representations across different sentences", then the cosine);
+ *   mode 1: average over the sentences of the per-sentence cosine (the procedure's name).
+ * A zero vector contributes a cosine of 0.  The caller compares the result with the
+ * threshold T inside its kvs_accept_fn (keep the pair iff similarity > T).
+ * workspace >= kvs_cos_sim_workspace_bytes(S).
+ */
+int kvs_avg_cos_sim(const void* hidden_shared, const void* hidden_original, int S, size_t N,
+                    int dtype, int mode, float* similarity,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+size_t kvs_cos_sim_workspace_bytes(int S);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTS = [
     "kvs_last_error", "kvs_build_share_map", "kvs_validate_share_map", "kvs_slots_from_share_map",
     "kvs_store_bytes", "kvs_workspace_bytes", "kvs_append_kv", "kvs_gather_kv",
     "kvs_decode_attention", "kvs_prefill_attention", "kvs_set_split_tokens",
-    "kvs_layer_distance", "kvs_distance_workspace_bytes",
+    "kvs_layer_distance", "kvs_distance_workspace_bytes", "kvs_avg_cos_sim", "kvs_cos_sim_workspace_bytes",
 ]
 
 
@@ -79,6 +79,10 @@ def lib():
         L.kvs_set_split_tokens.argtypes = [C.c_int]
         L.kvs_layer_distance.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_size_t, C.c_int, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.kvs_cos_sim_workspace_bytes.restype = C.c_size_t
+        L.kvs_cos_sim_workspace_bytes.argtypes = [C.c_int]
+        L.kvs_avg_cos_sim.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_size_t, C.c_int, C.c_int, C.c_void_p,
+                                      C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
 
@@ -264,3 +268,23 @@ def kvs_layer_distance(kv_samples, workspace=None):
                                     outs[1].data_ptr(), outs[2].data_ptr(), workspace.data_ptr(),
                                     workspace.numel(), _stream()))
     return tuple(outs)
+
+
+# ------------------------------------------------------------------ similarity test
+
+def kvs_avg_cos_sim(hidden_shared, hidden_original, mode=0, workspace=None):
+    """hidden_*: device [S, N] (bf16 or fp32), same shape and dtype. Returns a device fp32 scalar tensor."""
+    a, b = hidden_shared, hidden_original
+    assert a.is_cuda and b.is_cuda and a.is_contiguous() and b.is_contiguous()
+    assert a.shape == b.shape and a.dtype == b.dtype and a.dim() == 2
+    assert a.dtype in (torch.bfloat16, torch.float32)
+    S, N = a.shape
+    need = lib().kvs_cos_sim_workspace_bytes(int(S))
+    if need == 0:
+        raise KvsError(KVS_ERR_INVALID_ARG, last_error())
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
+    out = torch.empty(1, dtype=torch.float32, device=a.device)
+    _check(lib().kvs_avg_cos_sim(a.data_ptr(), b.data_ptr(), S, N, KVS_BF16 if a.dtype == torch.bfloat16 else KVS_F32,
+                                 int(mode), out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    return out

@@ -383,4 +383,25 @@ int kvs_layer_distance(const void* kv_samples, int S, int L, size_t N, int dtype
     return KVS_OK;
 }
 
+size_t kvs_cos_sim_workspace_bytes(int S)
+{
+    if (S <= 0 || S > 65535) { fail(KVS_ERR_INVALID_ARG, "S must be in [1, 65535]"); return 0; }
+    return kvs::cos_sim_workspace_bytes(S);
+}
+
+int kvs_avg_cos_sim(const void* hidden_shared, const void* hidden_original, int S, size_t N, int dtype, int mode,
+                    float* similarity, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!hidden_shared || !hidden_original || !similarity) return fail(KVS_ERR_INVALID_ARG, "NULL argument");
+    if (S <= 0 || S > 65535 || N == 0) return fail(KVS_ERR_INVALID_ARG, "need 0 < S <= 65535 and N > 0");
+    if (dtype != KVS_F32 && dtype != KVS_BF16) return fail(KVS_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    if (mode != 0 && mode != 1) return fail(KVS_ERR_INVALID_ARG, "mode must be 0 (mean first) or 1 (per sentence)");
+    const size_t need = kvs::cos_sim_workspace_bytes(S);
+    if (!workspace || workspace_bytes < need)
+        return fail(KVS_ERR_INVALID_ARG, "workspace too small: need %zu bytes, got %zu", need, workspace_bytes);
+    if (int e = kvs::launch_cos_sim(hidden_shared, hidden_original, S, N, dtype, mode, similarity, workspace, stream))
+        return fail(KVS_ERR_HIP, "similarity launch: %s", kvs::hip_error_string(e));
+    return KVS_OK;
+}
+
 }  // extern "C"

@@ -41,6 +41,9 @@ int launch_attention(const AttnArgs& a, void* stream);
 int launch_layer_distance(const void* kv, int S, int L, size_t N, int dtype, float* dK2, float* dV2,
                           float* D, void* workspace, void* stream);
 size_t distance_workspace_bytes(int L);
+int launch_cos_sim(const void* a, const void* b, int S, size_t N, int dtype, int mode, float* out, void* workspace,
+                   void* stream);
+size_t cos_sim_workspace_bytes(int S);
 const char* hip_error_string(int err);
 
 }  // namespace kvs
