@@ -35,8 +35,8 @@ __device__ __forceinline__ int resolve_slot(const StoreView& st)
 // Physical block of logical page `page` of sequence b.
 __device__ __forceinline__ int block_of(const StoreView& st, int b, int page)
 {
-    const int idx = b * st.max_blocks_per_seq + page;
-    return st.block_table ? st.block_table[idx] : idx;
+    const size_t idx = (size_t)b * st.max_blocks_per_seq + page;
+    return st.block_table ? st.block_table[idx] : (int)idx;   // contiguous: the host checked B * max_blocks <= num_blocks
 }
 
 // Same, forced into the pool: a corrupt table entry must not turn into a wild read.

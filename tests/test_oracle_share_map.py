@@ -88,3 +88,22 @@ def test_seeded_maps_are_valid_depth_one():
         assert int((m != np.arange(w.L)).sum()) == w.n_shared
         assert all(m[l] <= l and m[m[l]] == m[l] for l in range(w.L))
         assert inputs.slots_of(m)[1] == w.L - w.n_shared
+
+
+def test_layer_counts_of_the_main_results_table():
+    """Golden values printed by the paper: with C = rate * L shared layers, L - C caches remain."""
+    import os
+    from paper_2410_18517_amd import binding as kb
+    path = os.path.join(os.path.dirname(__file__), "golden", "layer_counts.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 5
+    rng = np.random.default_rng(11)
+    for model, full, *kept in rows:
+        L = int(full)
+        for rate, want in zip((0.125, 0.25, 0.375), map(int, kept)):
+            C = int(round(rate * L))
+            A = rng.random((L, L)).astype(np.float32); D = A + A.T; np.fill_diagonal(D, 0)
+            st, share, slot, n_slots, n = osm.build_share_map(D, L, C)
+            assert st == 0 and n_slots == want == L - C, (model, rate)
+            got = kb.kvs_build_share_map(D, C)
+            assert got[3] == want and got[1].tolist() == share
