@@ -124,6 +124,64 @@ __global__ void copy_rows_kernel(CopyArgs a)
     }
 }
 
+// Append of several rows per sequence to a bf16 store (prefill chunks, store fills): one
+// workgroup per (sequence, kv head, page touched).  K rows go straight to their operand-order
+// position, 16 bytes per thread.  V rows are staged in LDS and leave as whole 16-byte operand
+// chunks (four tokens x two channels) wherever all four tokens of the chunk are being written;
+// the ragged first and last tokens of the append fall back to 2-byte stores.  A whole-page
+// append therefore writes each page as 4 KiB of full-width stores instead of 2-byte scatters.
+__global__ __launch_bounds__(256) void append_pages_bf16_kernel(CopyArgs a)
+{
+    const StoreView& st = a.st;
+    const int D = st.head_dim;                    // 64 or 128
+    const int g = blockIdx.y, b = blockIdx.z;
+    const long start = a.start_pos[b];
+    const long cap = (long)st.max_blocks_per_seq * kPageTokens;
+    if (start < 0 || start >= cap) return;
+    const long end = start + a.T < cap ? start + a.T : cap;
+    const long page = start / kPageTokens + blockIdx.x;
+    const long tok0 = page * kPageTokens;
+    if (tok0 >= end) return;
+    const int t_lo = (int)(start > tok0 ? start - tok0 : 0);
+    const int t_hi = (int)(end - tok0 < kPageTokens ? end - tok0 : kPageTokens);
+    const int blk = block_of(st, b, (int)page);
+    if (blk < 0 || blk >= st.num_blocks) return;
+    unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, resolve_slot(st), blk, g);
+    unsigned short* vp = kp + kPageTokens * D;
+    __shared__ unsigned short vs[kPageTokens][128 + 8];
+
+    const int chunks = D / 8;                     // 16-byte chunks per row
+    const int t = threadIdx.x / 16, ch = threadIdx.x % 16;
+    if (t >= t_lo && t < t_hi && ch < chunks) {
+        const size_t row = (((size_t)b * a.T + (size_t)(tok0 + t - start)) * st.Hkv + g) * D + (size_t)ch * 8;
+        *reinterpret_cast<uint4*>(kp + k_index_bf16(t, ch * 8)) =
+            *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(a.k) + row);
+        *reinterpret_cast<uint4*>(&vs[t][ch * 8]) =
+            *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(a.v) + row);
+    }
+    __syncthreads();
+    // output chunk o: channels (o/64)*32 + {0,16} + o%16, tokens 4*((o/16)%4) .. +3
+    for (int o = threadIdx.x; o < D * 2; o += 256) {
+        const int cp = o / 64, quad = (o / 16) % 4, dl = o % 16;
+        unsigned short e[8];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) e[j * 4 + i] = vs[quad * 4 + i][cp * 32 + j * 16 + dl];
+        unsigned short* dst = vp + (size_t)o * 8;
+        if (quad * 4 >= t_lo && quad * 4 + 4 <= t_hi) {
+            *reinterpret_cast<uint4*>(dst) = make_uint4(e[0] | (unsigned)e[1] << 16, e[2] | (unsigned)e[3] << 16,
+                                                        e[4] | (unsigned)e[5] << 16, e[6] | (unsigned)e[7] << 16);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (quad * 4 + i >= t_lo && quad * 4 + i < t_hi) dst[j * 4 + i] = e[j * 4 + i];
+        }
+    }
+}
+
 // ------------------------------------------------------------------ fp32 store
 // One wavefront per (sequence, query row, query head); the whole context in one pass.
 // Lanes own tokens for the scores and channels for the weighted sum.
@@ -626,6 +684,13 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
 
 int launch_append(const CopyArgs& a, void* stream)
 {
+    if (a.st.dtype == 1 && a.T >= 4) {
+        // pages a sequence's rows can touch: T rows starting anywhere inside a page
+        const unsigned pages = (unsigned)((a.T + kPageTokens - 1) / kPageTokens + 1);
+        hipLaunchKernelGGL(append_pages_bf16_kernel, dim3(pages, a.st.Hkv, a.B), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), a);
+        return (int)hipGetLastError();
+    }
     const int per = a.st.dtype == 1 ? 8 : 4;
     const long total = (long)a.B * a.T * a.st.Hkv * (a.st.head_dim / per);
     const unsigned blocks = (unsigned)((total + 255) / 256);

@@ -277,6 +277,7 @@ int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const vo
                     store->desc.max_blocks_per_seq * KVS_BLOCK_TOKENS);
     if (!store->block_table && (long)B * store->desc.max_blocks_per_seq > store->desc.num_blocks)
         return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
+    if (B > 65535 || store->desc.Hkv > 65535) return fail(KVS_ERR_CAPACITY, "B and Hkv are limited to 65535");
     if (store->host_share_map[layer] != layer) return KVS_NOOP;   // the layer reads its donor's cache
     kvs::CopyArgs a;
     a.st = view_of(store, layer);
