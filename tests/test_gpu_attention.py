@@ -189,3 +189,40 @@ def test_causal_prefill(kb, dtype, Hq, Hkv, d, T_new):
     dec = kb.kvs_decode_attention(case.store, 0, q[:, -1].contiguous().cuda(),
                                   np.array([10, 20, 30], np.int32) + T_new)
     assert rel_l2_rows(dec.cpu().numpy(), pre[:, -1].cpu().numpy().astype(np.float64)).max() <= REL_L2_ATTENTION
+
+
+def test_randomised_shapes_maps_and_lengths(kb):
+    """Seeded sweep over store types, head groupings, batch sizes, sharing maps, paging, split sizes
+    and ragged lengths; every case is compared element by element with the oracle."""
+    rng = np.random.default_rng(20241018)
+    try:
+        for case_id in range(24):
+            dtype = "bf16" if case_id % 4 else "f32"
+            d = int(rng.choice([64, 128]))
+            Hkv = int(rng.choice([1, 2, 3, 8]))
+            group = int(rng.choice([1, 2, 4, 7, 16] if dtype == "bf16" else [1, 3]))
+            L = int(rng.integers(2, 7))
+            B = int(rng.integers(1, 9))
+            cap = int(rng.choice([40, 130, 517, 1200]))
+            share = inputs.make_share_map(L, int(rng.integers(0, L)), 900 + case_id)
+            case = Case(kb, L, Hkv * group, Hkv, d, B, dtype, cap, share, paged=bool(rng.integers(0, 2)),
+                        seed=900 + case_id)
+            lens = rng.integers(0, cap + 1, size=B).astype(np.int32)
+            lens[rng.integers(0, B)] = cap
+            kb.kvs_set_split_tokens(int(rng.choice([0, 64, 256, 1024])))
+            tol = 1e-5 if dtype == "f32" else REL_L2_ATTENTION
+            for layer in rng.choice(L, size=min(L, 3), replace=False):
+                q = case.q(int(layer))
+                got = kb.kvs_decode_attention(case.store, int(layer), q.cuda(), lens).cpu().numpy()
+                want = orc.decode_attention(int(layer), share, case.K, case.V, inputs.to_oracle_array(q), lens)
+                assert np.isfinite(got).all()
+                assert rel_l2_rows(got, want).max() <= tol, (case_id, dtype, d, Hkv, group, L, B, cap, int(layer))
+            T_new = int(rng.integers(2, min(cap, 70)))
+            start = rng.integers(0, cap - T_new + 1, size=B).astype(np.int32)
+            layer = int(rng.integers(0, L))
+            q = case.q(layer, rows=T_new)
+            got = kb.kvs_prefill_attention(case.store, layer, q.cuda(), start).cpu().numpy()
+            want = orc.shared_attention(layer, share, case.K, case.V, inputs.to_oracle_array(q), start)
+            assert rel_l2_rows(got, want).max() <= tol, (case_id, "prefill", T_new)
+    finally:
+        kb.kvs_set_split_tokens(0)
