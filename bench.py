@@ -133,6 +133,57 @@ def bench_distance(args, torch, kb, inputs, dev):
                      "algorithmic_bytes": nbytes}}))
 
 
+def bench_project(args, torch, kb, inputs, dev):
+    """Fused K/V projection + rotary embedding + append of one decode step, Llama-3-8B shape
+    (hidden 4096, 8 kv heads x 128): the per-layer work that sharing removes for recipient layers."""
+    w = inputs.WORKLOADS["llama3-8b-32k"]
+    hidden, n_layers = 4096, 4                             # rotate over four layers' weights
+    mb = w.max_blocks_per_seq
+    store = kb.KVStore(np.arange(n_layers, dtype=np.int32), w.Hq, w.Hkv, w.d, "bf16", w.B * mb, mb)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_BASE)
+    n_out = w.Hkv * w.d
+    wk = [(torch.randn((n_out, hidden), device=dev, generator=gen) / 64).bfloat16() for _ in range(n_layers)]
+    wv = [(torch.randn((n_out, hidden), device=dev, generator=gen) / 64).bfloat16() for _ in range(n_layers)]
+    x = torch.randn((w.B, 1, hidden), device=dev, generator=gen).bfloat16()
+    ang = torch.outer(torch.arange(w.context, dtype=torch.float64),
+                      10000.0 ** (-torch.arange(w.d // 2, dtype=torch.float64) * 2 / w.d))
+    cos, sin = torch.cos(ang).float().to(dev), torch.sin(ang).float().to(dev)
+    pos = torch.full((w.B,), w.context - 1, dtype=torch.int32, device=dev)
+    reps = 8
+
+    def one_round():                                       # all four layers back to back
+        for l in range(n_layers):
+            kb.kvs_project_append_kv(store, l, x, wk[l], wv[l], pos, cos, sin)
+
+    one_round()                                            # eager: sizes the workspace, gives the expected rows
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in kb.kvs_gather_kv(store, 0, w.context - 1, 1, w.B)]
+    # The kernel is a few microseconds, less than one call through the interpreter, so the launches
+    # are recorded once into a HIP graph (kernel nodes only) and the replays are timed.
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(reps):
+            one_round()
+    us = _event_time_us(torch, graph.replay, args.steps, args.warmup) / (reps * n_layers)
+    replayed = kb.kvs_gather_kv(store, 0, w.context - 1, 1, w.B)
+    if not all(torch.equal(a, b) for a, b in zip(eager, replayed)):
+        raise SystemExit("graph replays wrote different rows than the eager launches")
+    nbytes = 2 * n_out * hidden * 2 + w.B * hidden * 2 + w.B * 2 * n_out * 2
+    flops = 2.0 * w.B * 2 * n_out * hidden
+    achieved = nbytes / us / 1e3
+    print(json.dumps({
+        "metric": "fused K/V projection + rotary + append, layers/s", "value": round(1e6 / us, 1), "unit": "layers/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us * 1e-3, 5),
+        "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama3-8b decode projection", "batch": w.B, "hidden": hidden, "kv_heads": w.Hkv,
+                   "head_dim": w.d},
+        "saved_per_recipient_layer": {"weight_bytes": 2 * n_out * hidden * 2, "flops": flops, "us": round(us, 2)},
+        "roofline": {"bound": "hbm", "kernel": "project_append_bf16_kernel", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": None, "launch_us": round(us, 2), "algorithmic_bytes": nbytes}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,7 +192,7 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split-tokens", type=int, default=0)
-    ap.add_argument("--mode", choices=["decode", "prefill", "distance"], default="decode",
+    ap.add_argument("--mode", choices=["decode", "prefill", "distance", "project"], default="decode",
                     help="decode (default): the whole decode step, the headline metric.  prefill: the 64-row "
                          "causal chunk of the llama2-13b workload.  distance: the 48-layer calibration matrix. "
                          "The last two time the other kernels of the path, one JSON line each.")
@@ -164,6 +215,8 @@ def main():
         return bench_prefill(args, torch, kb, inputs, dev)
     if args.mode == "distance":
         return bench_distance(args, torch, kb, inputs, dev)
+    if args.mode == "project":
+        return bench_project(args, torch, kb, inputs, dev)
     w = inputs.WORKLOADS[args.workload]
 
     share = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)

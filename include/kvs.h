@@ -137,6 +137,29 @@ int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const vo
                   const int32_t* start_pos, int B, int T_new, void* stream);
 
 /*
+ * Key/value projection fused with the append: the computation a sharing strategy removes for
+ * every layer that reads a donor's cache (Sec. 3.2; the abstract's "KV cache computation").
+ * For a layer that keeps its own cache, with x device [B][T_new][hidden] and the projection
+ * weights w_k, w_v device [Hkv*head_dim][hidden] (row = output channel, bf16):
+ *     k = x . w_k^T,   v = x . w_v^T                      (fp32 accumulation)
+ *     k[c], k[c+h] <- k[c] cos - k[c+h] sin,  k[c+h] cos + k[c] sin      h = head_dim/2, c < h,
+ *          cos = rope_cos[p][c], sin = rope_sin[p][c], p = start_pos[b] + i  (skipped if NULL)
+ *     rounded to bf16 (nearest even) and stored at position p of the layer's slot.
+ * rope_cos, rope_sin: device fp32 [rope_positions][head_dim/2], rope_positions >= capacity.
+ * bf16 stores only; hidden a multiple of 128.  workspace: device, >=
+ * kvs_project_workspace_bytes(), zero-filled once by the caller and left zero by every call
+ * (it holds arrival counters and partial sums of the split contraction); calls sharing it must
+ * not overlap.  Returns KVS_NOOP without touching the GPU when the layer reads a donor's cache.
+ */
+int kvs_project_append_kv(const kvs_store* store, int layer, const void* x, int hidden,
+                          const void* w_k, const void* w_v,
+                          const float* rope_cos, const float* rope_sin, int rope_positions,
+                          const int32_t* start_pos, int B, int T_new,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+size_t kvs_project_workspace_bytes(const kvs_desc* desc, int hidden, int B, int T_new);
+
+/*
  * Read back T tokens starting at t0 of every sequence from the cache `layer` attends to
  * (its donor's when it has one), in the order kvs_append_kv takes:
  * k_out, v_out device [B][T][Hkv][head_dim].  Inverse of kvs_append_kv; for checks, cache

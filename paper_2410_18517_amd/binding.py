@@ -24,6 +24,7 @@ EXPORTS = [
     "kvs_store_bytes", "kvs_workspace_bytes", "kvs_append_kv", "kvs_gather_kv",
     "kvs_decode_attention", "kvs_prefill_attention", "kvs_set_split_tokens",
     "kvs_layer_distance", "kvs_distance_workspace_bytes", "kvs_avg_cos_sim", "kvs_cos_sim_workspace_bytes",
+    "kvs_project_append_kv", "kvs_project_workspace_bytes",
 ]
 
 
@@ -79,6 +80,11 @@ def lib():
         L.kvs_set_split_tokens.argtypes = [C.c_int]
         L.kvs_layer_distance.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_size_t, C.c_int, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.kvs_project_append_kv.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                            C.c_void_p, C.c_size_t, C.c_void_p]
+        L.kvs_project_workspace_bytes.restype = C.c_size_t
+        L.kvs_project_workspace_bytes.argtypes = [C.POINTER(kvs_desc), C.c_int, C.c_int, C.c_int]
         L.kvs_cos_sim_workspace_bytes.restype = C.c_size_t
         L.kvs_cos_sim_workspace_bytes.argtypes = [C.c_int]
         L.kvs_avg_cos_sim.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_size_t, C.c_int, C.c_int, C.c_void_p,
@@ -208,6 +214,38 @@ def kvs_append_kv(store: KVStore, layer, k_new, v_new, start_pos) -> int:
     assert sp.numel() == B
     return _check(lib().kvs_append_kv(C.byref(store.c), int(layer), k_new.data_ptr(), v_new.data_ptr(),
                                       sp.data_ptr(), B, T_new, _stream()), ok=(KVS_OK, KVS_NOOP))
+
+
+def kvs_project_append_kv(store: KVStore, layer, x, w_k, w_v, start_pos, rope_cos=None, rope_sin=None,
+                          workspace=None) -> int:
+    """x: device bf16 [B, T_new, hidden]; w_k, w_v: device bf16 [Hkv*d, hidden]; rope tables device fp32
+    [positions, d/2] or None. Returns KVS_OK or KVS_NOOP."""
+    for t in (x, w_k, w_v):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16
+    B, T_new, hidden = x.shape
+    n_out = store.desc.Hkv * store.desc.head_dim
+    assert tuple(w_k.shape) == (n_out, hidden) == tuple(w_v.shape)
+    positions = 0
+    if rope_cos is not None:
+        assert rope_cos.is_cuda and rope_cos.dtype == torch.float32 and rope_cos.is_contiguous()
+        assert rope_sin is not None and rope_sin.shape == rope_cos.shape and rope_sin.dtype == torch.float32
+        assert rope_cos.shape[1] == store.desc.head_dim // 2
+        positions = rope_cos.shape[0]
+    sp = _dev_i32(start_pos, store.device)
+    assert sp.numel() == B
+    if workspace is None:
+        need = lib().kvs_project_workspace_bytes(C.byref(store.desc), int(hidden), int(B), int(T_new))
+        if need == 0:
+            raise KvsError(KVS_ERR_INVALID_ARG, last_error())
+        ws = getattr(store, "_proj_ws", None)
+        if ws is None or ws.numel() < need:
+            ws = store._proj_ws = torch.zeros(need, dtype=torch.uint8, device=store.device)
+        workspace = ws
+    return _check(lib().kvs_project_append_kv(
+        C.byref(store.c), int(layer), x.data_ptr(), int(hidden), w_k.data_ptr(), w_v.data_ptr(),
+        rope_cos.data_ptr() if rope_cos is not None else None,
+        rope_sin.data_ptr() if rope_sin is not None else None, int(positions),
+        sp.data_ptr(), int(B), int(T_new), workspace.data_ptr(), workspace.numel(), _stream()), ok=(KVS_OK, KVS_NOOP))
 
 
 def kvs_gather_kv(store: KVStore, layer, t0, T, B):

@@ -291,6 +291,55 @@ int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const vo
     return KVS_OK;
 }
 
+int kvs_project_append_kv(const kvs_store* store, int layer, const void* x, int hidden, const void* w_k,
+                          const void* w_v, const float* rope_cos, const float* rope_sin, int rope_positions,
+                          const int32_t* start_pos, int B, int T_new, void* workspace, size_t workspace_bytes,
+                          void* stream)
+{
+    if (int rc = check_store(store, layer)) return rc;
+    if (!x || !w_k || !w_v || !start_pos) return fail(KVS_ERR_INVALID_ARG, "x, w_k, w_v or start_pos is NULL");
+    if ((rope_cos == nullptr) != (rope_sin == nullptr))
+        return fail(KVS_ERR_INVALID_ARG, "rope_cos and rope_sin must be given together");
+    if (store->desc.dtype != KVS_BF16) return fail(KVS_ERR_UNSUPPORTED, "the fused projection needs a bf16 store");
+    if (hidden <= 0 || hidden % 128 != 0) return fail(KVS_ERR_UNSUPPORTED, "hidden must be a positive multiple of 128 (got %d)", hidden);
+    if (B <= 0 || T_new <= 0) return fail(KVS_ERR_INVALID_ARG, "B and T_new must be positive (B=%d, T_new=%d)", B, T_new);
+    const long capacity = (long)store->desc.max_blocks_per_seq * KVS_BLOCK_TOKENS;
+    if (T_new > capacity) return fail(KVS_ERR_CAPACITY, "T_new=%d exceeds the per-sequence capacity %ld", T_new, capacity);
+    if (rope_cos && rope_positions < capacity)
+        return fail(KVS_ERR_CAPACITY, "rotary tables cover %d positions, the store holds %ld per sequence", rope_positions, capacity);
+    if ((long)B * T_new > (1L << 30) || ((long)B * T_new + 15) / 16 > 65535)
+        return fail(KVS_ERR_CAPACITY, "B * T_new is limited to 16 * 65535 rows per call");
+    if (!store->block_table && (long)B * store->desc.max_blocks_per_seq > store->desc.num_blocks)
+        return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
+    if (store->host_share_map[layer] != layer) return KVS_NOOP;   // the work sharing saves
+    const size_t need = kvs::project_workspace_bytes(store->desc.Hkv, store->desc.head_dim, hidden, B * T_new);
+    if (!workspace || workspace_bytes < need)
+        return fail(KVS_ERR_INVALID_ARG, "workspace too small: need %zu bytes, got %zu", need, workspace_bytes);
+    kvs::ProjectArgs a;
+    a.st = view_of(store, layer);
+    a.x = x;
+    a.w_k = w_k;
+    a.w_v = w_v;
+    a.rope_cos = rope_cos;
+    a.rope_sin = rope_sin;
+    a.start_pos = start_pos;
+    a.hidden = hidden;
+    a.B = B;
+    a.T = T_new;
+    if (int e = kvs::launch_project_append(a, workspace, stream)) return fail(KVS_ERR_HIP, "projection launch: %s", kvs::hip_error_string(e));
+    return KVS_OK;
+}
+
+size_t kvs_project_workspace_bytes(const kvs_desc* d, int hidden, int B, int T_new)
+{
+    if (check_desc(d) != KVS_OK) return 0;
+    if (d->dtype != KVS_BF16 || hidden <= 0 || hidden % 128 != 0 || B <= 0 || T_new <= 0 || (long)B * T_new > (1L << 30)) {
+        fail(KVS_ERR_INVALID_ARG, "bf16 store, hidden a positive multiple of 128, B and T_new positive");
+        return 0;
+    }
+    return kvs::project_workspace_bytes(d->Hkv, d->head_dim, hidden, B * T_new);
+}
+
 int kvs_gather_kv(const kvs_store* store, int layer, int t0, int T, int B,
                   void* k_out, void* v_out, void* stream)
 {

@@ -34,10 +34,26 @@ struct CopyArgs {
     int32_t t0, B, T;
 };
 
+struct ProjectArgs {
+    StoreView st;
+    const void* x;          // device [B][T][hidden], bf16
+    const void* w_k;        // device [Hkv*D][hidden], bf16
+    const void* w_v;
+    const float* rope_cos;  // device [positions][D/2] or nullptr
+    const float* rope_sin;
+    const int32_t* start_pos;  // device [B]
+    int32_t hidden, B, T;
+    int32_t k_splits;       // workgroups sharing one output tile's contraction (set by the launcher)
+    int32_t* counters;      // device, one per output tile, zero between calls
+    float* partials;        // device [k_splits][tiles][256][2]
+};
+
 // Each returns hipError_t as int (0 = success) after enqueueing on `stream`.
 int launch_append(const CopyArgs& a, void* stream);
 int launch_gather(const CopyArgs& a, void* stream);
 int launch_attention(const AttnArgs& a, void* stream);
+int launch_project_append(ProjectArgs a, void* workspace, void* stream);
+size_t project_workspace_bytes(int Hkv, int head_dim, int hidden, int rows);
 int launch_layer_distance(const void* kv, int S, int L, size_t N, int dtype, float* dK2, float* dV2,
                           float* D, void* workspace, void* stream);
 size_t distance_workspace_bytes(int L);

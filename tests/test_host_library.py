@@ -93,6 +93,14 @@ def test_store_and_workspace_sizes():
         assert kb.last_error()
     assert lib.kvs_workspace_bytes(C.byref(d), 0, 1) == 0
     assert lib.kvs_distance_workspace_bytes(65) == 0 and lib.kvs_distance_workspace_bytes(48) > 0
+    # projection: 2*Hkv*(d/32) output tiles per 16 rows, one counter each (padded to 256 bytes), and
+    # when the contraction is split, one 256-thread pair of floats per tile and split
+    big = _desc(Hq=32, Hkv=8)
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 4, 1) == 256 + 4 * 64 * 256 * 8
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 128, 4, 1) == 256          # nothing to split
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 64, 64) == 64 * 256 * 4   # enough tiles already
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 100, 4, 1) == 0
+    assert lib.kvs_project_workspace_bytes(C.byref(_desc(dtype=kb.KVS_F32)), 4096, 4, 1) == 0
 
 
 def _fake_store(share=(0, 1, 2, 1), slots=(0, 1, 2, 1), **kw):
@@ -138,6 +146,21 @@ def test_entry_points_reject_bad_arguments_without_touching_the_gpu():
     finally:
         assert lib.kvs_set_split_tokens(0) == kb.KVS_OK
     assert lib.kvs_set_split_tokens(100) == kb.KVS_ERR_INVALID_ARG
+    # fused projection: recipient layers are a host-side no-op; bad shapes and a missing workspace are errors
+    proj = lambda layer, hidden=256, cos=None, sin=None, npos=0, B=1, T=1, ws=p, nws=1 << 30, x=p: \
+        lib.kvs_project_append_kv(C.byref(st), layer, x, hidden, p, p, cos, sin, npos, p, B, T, ws, nws, None)
+    assert proj(3) == kb.KVS_NOOP
+    assert proj(4) == kb.KVS_ERR_INVALID_ARG
+    assert proj(0, x=None) == kb.KVS_ERR_INVALID_ARG
+    assert proj(0, hidden=200) == kb.KVS_ERR_UNSUPPORTED
+    assert proj(0, cos=p) == kb.KVS_ERR_INVALID_ARG                      # one rotary table without the other
+    assert proj(0, cos=p, sin=p, npos=63) == kb.KVS_ERR_CAPACITY         # tables shorter than the 64-token capacity
+    assert proj(0, T=65) == kb.KVS_ERR_CAPACITY
+    assert proj(0, B=0) == kb.KVS_ERR_INVALID_ARG
+    assert proj(0, ws=None) == kb.KVS_ERR_INVALID_ARG
+    assert proj(0, nws=8) == kb.KVS_ERR_INVALID_ARG and "workspace" in kb.last_error()
+    assert lib.kvs_project_append_kv(C.byref(_fake_store(dtype=kb.KVS_F32, head_dim=64)), 0, p, 256, p, p, None, None, 0,
+                                     p, 1, 1, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
     # distance
     assert lib.kvs_layer_distance(None, 1, 2, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_layer_distance(p, 1, 65, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
