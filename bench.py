@@ -18,7 +18,8 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published peak
+HBM_PEAK_GBPS = 8000.0              # MI355X HBM3E, published peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak, published
 
 
 def algorithmic_bytes_per_launch(w, seq_lens):
@@ -134,8 +135,10 @@ def bench_distance(args, torch, kb, inputs, dev):
 
 
 def bench_project(args, torch, kb, inputs, dev):
-    """Fused K/V projection + rotary embedding + append of one decode step, Llama-3-8B shape
-    (hidden 4096, 8 kv heads x 128): the per-layer work that sharing removes for recipient layers."""
+    """Fused K/V projection + rotary embedding + append, Llama-3-8B shape (hidden 4096, 8 kv heads
+    x 128): the per-layer work that sharing removes for recipient layers.  One new row per
+    sequence (a decode step) streams the weights and is priced against HBM; --project-rows T > 1
+    (a prefill chunk of T rows per sequence) is a matrix product priced against the bf16 MFMA peak."""
     w = inputs.WORKLOADS["llama3-8b-32k"]
     hidden, n_layers = 4096, 4                             # rotate over four layers' weights
     mb = w.max_blocks_per_seq
@@ -145,12 +148,13 @@ def bench_project(args, torch, kb, inputs, dev):
     n_out = w.Hkv * w.d
     wk = [(torch.randn((n_out, hidden), device=dev, generator=gen) / 64).bfloat16() for _ in range(n_layers)]
     wv = [(torch.randn((n_out, hidden), device=dev, generator=gen) / 64).bfloat16() for _ in range(n_layers)]
-    x = torch.randn((w.B, 1, hidden), device=dev, generator=gen).bfloat16()
+    T = args.project_rows
+    x = torch.randn((w.B, T, hidden), device=dev, generator=gen).bfloat16()
     ang = torch.outer(torch.arange(w.context, dtype=torch.float64),
                       10000.0 ** (-torch.arange(w.d // 2, dtype=torch.float64) * 2 / w.d))
     cos, sin = torch.cos(ang).float().to(dev), torch.sin(ang).float().to(dev)
-    pos = torch.full((w.B,), w.context - 1, dtype=torch.int32, device=dev)
-    reps = 8
+    pos = torch.full((w.B,), w.context - T, dtype=torch.int32, device=dev)
+    reps = 8 if T == 1 else 1
 
     def one_round():                                       # all four layers back to back
         for l in range(n_layers):
@@ -169,19 +173,25 @@ def bench_project(args, torch, kb, inputs, dev):
     replayed = kb.kvs_gather_kv(store, 0, w.context - 1, 1, w.B)
     if not all(torch.equal(a, b) for a, b in zip(eager, replayed)):
         raise SystemExit("graph replays wrote different rows than the eager launches")
-    nbytes = 2 * n_out * hidden * 2 + w.B * hidden * 2 + w.B * 2 * n_out * 2
-    flops = 2.0 * w.B * 2 * n_out * hidden
-    achieved = nbytes / us / 1e3
+    rows = w.B * T
+    nbytes = 2 * n_out * hidden * 2 + rows * hidden * 2 + rows * 2 * n_out * 2
+    flops = 2.0 * rows * 2 * n_out * hidden
+    if T == 1:
+        roof = {"bound": "hbm", "kernel": "project_append_bf16_kernel", "achieved": round(nbytes / us / 1e3, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
+    else:
+        roof = {"bound": "mfma", "kernel": "project_append_tiled_kernel<128>", "achieved": round(flops / us / 1e6, 1),
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    roof.update({"traffic": None, "launch_us": round(us, 2), "algorithmic_bytes": nbytes, "algorithmic_flops": flops})
     print(json.dumps({
         "metric": "fused K/V projection + rotary + append, layers/s", "value": round(1e6 / us, 1), "unit": "layers/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us * 1e-3, 5),
         "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "llama3-8b decode projection", "batch": w.B, "hidden": hidden, "kv_heads": w.Hkv,
-                   "head_dim": w.d},
+        "config": {"workload": "llama3-8b decode projection" if T == 1 else "llama3-8b prefill projection",
+                   "batch": w.B, "rows_per_sequence": T, "hidden": hidden, "kv_heads": w.Hkv, "head_dim": w.d},
         "saved_per_recipient_layer": {"weight_bytes": 2 * n_out * hidden * 2, "flops": flops, "us": round(us, 2)},
-        "roofline": {"bound": "hbm", "kernel": "project_append_bf16_kernel", "achieved": round(achieved, 1),
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": None, "launch_us": round(us, 2), "algorithmic_bytes": nbytes}}))
+        "roofline": roof}))
 
 
 def main():
@@ -192,6 +202,8 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--project-rows", type=int, default=1,
+                    help="--mode project: new rows per sequence (1 = decode step, more = prefill chunk)")
     ap.add_argument("--mode", choices=["decode", "prefill", "distance", "project"], default="decode",
                     help="decode (default): the whole decode step, the headline metric.  prefill: the 64-row "
                          "causal chunk of the llama2-13b workload.  distance: the 48-layer calibration matrix. "

@@ -13,8 +13,15 @@
 // of rows) is a weight-streaming problem bounded by HBM; to put enough workgroups on it the
 // contraction is also split across workgroups (grid.z): each publishes its partial tile with
 // device-scope stores and the last to arrive at a tile adds them in a fixed order and finishes
-// (same no-wait protocol as the attention splits).  A prefill chunk re-reads the strips from
-// L2 once per 16 rows.
+// (same no-wait protocol as the attention splits).
+//
+// A prefill chunk (more than 32 rows) is a matrix product bounded by the matrix cores and takes
+// the tiled kernel instead: a workgroup of eight wavefronts owns 256 rows and one whole head of
+// K or V, stages 256 x 64 pieces of x and 128 x 64 pieces of the head's weight rows through
+// double-buffered LDS (the 16-byte pieces of a row are XOR-swizzled by the row index, so that the
+// operand reads of a wavefront fall on distinct banks without padding), and each wavefront keeps
+// a 64 x (head_dim/2) block of accumulators whose columns again hold both ends of the rotary
+// pairs.  Global loads run two steps ahead of their use, operand reads half a step ahead.
 #include <hip/hip_runtime.h>
 
 #include "kvs_internal.h"
@@ -31,6 +38,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2;
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ unsigned short round_bf16(float x)
 {
@@ -186,41 +194,307 @@ __global__ __launch_bounds__(kThreads) void project_append_bf16_kernel(ProjectAr
     }
 }
 
+// ---- tiled kernel for many rows ------------------------------------------------------------
+
+constexpr int kTileRows = 256;         // rows of x per workgroup
+constexpr int kTiledThreads = 2 * kTileRows;   // a wavefront per 64 rows x half of the head's rotary pairs
+constexpr int kStageRows = kTiledThreads / 8;  // rows staged by one pass of the workgroup (8 threads per row)
+constexpr int kTileK = 64;             // contraction depth staged per step
+constexpr int kLdsRow = kTileK;        // elements per staged row; 16-byte piece q of row r sits at piece q ^ (r & 7)
+
+template <int D>
+__global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(ProjectArgs a)
+{
+    constexpr int NT = D / 32;         // 16-column accumulator tiles per wavefront: NT/2 low, NT/2 high channels
+    constexpr int half = D / 2;
+    constexpr int kBChunks = D * (kTileK / 8) / kTiledThreads;          // 16-byte pieces of the weight tile per thread
+    constexpr int kAChunks = kTileRows * (kTileK / 8) / kTiledThreads;  // and of the x tile
+    const StoreView& st = a.st;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int quad = lane >> 4, l16 = lane & 15;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int head = blockIdx.x % st.Hkv;
+    const int is_v = blockIdx.x / st.Hkv;
+    const int M = a.B * a.T;
+    const int m0 = blockIdx.y * kTileRows;
+
+    __shared__ __attribute__((aligned(16))) unsigned short sa[2][kTileRows][kLdsRow];
+    __shared__ __attribute__((aligned(16))) unsigned short sb[2][D][kLdsRow];
+
+    const unsigned short* x = static_cast<const unsigned short*>(a.x);
+    const unsigned short* w = static_cast<const unsigned short*>(is_v ? a.w_v : a.w_k) + (size_t)head * D * a.hidden;
+    const int k_len = a.hidden / a.k_splits;
+    const int k_begin = blockIdx.z * k_len;
+    const int n_steps = k_len / kTileK;
+
+    // Where each of the tile's rows will be stored: looked up once, by one thread per row, while
+    // the first tiles load (the epilogue then has no chain of dependent global loads per row).
+    __shared__ long long row_page[kTileRows];                      // element offset of the row's page, -1: dropped
+    __shared__ int row_pos[kTileRows];
+    if (threadIdx.x < kTileRows) {
+        const int m = m0 + threadIdx.x;
+        long long off = -1;
+        long pos = 0;
+        if (m < M) {
+            const int b = m / a.T;
+            pos = (long)a.start_pos[b] + m % a.T;
+            if (pos >= 0 && pos < (long)st.max_blocks_per_seq * kPageTokens) {
+                int donor = st.share_map[st.layer];
+                donor = donor < 0 ? 0 : (donor >= st.L ? st.L - 1 : donor);
+                int slot = st.slot_of_layer[donor];
+                slot = slot < 0 ? 0 : (slot >= st.n_slots ? st.n_slots - 1 : slot);
+                const size_t bidx = (size_t)b * st.max_blocks_per_seq + (size_t)(pos / kPageTokens);
+                const int blk = st.block_table ? st.block_table[bidx] : (int)bidx;
+                if (blk >= 0 && blk < st.num_blocks)
+                    off = (long long)(((((size_t)slot * st.num_blocks + blk) * st.Hkv + head) * 2 + is_v) *
+                                      (size_t)(kPageTokens * D));
+            }
+        }
+        row_page[threadIdx.x] = off;
+        row_pos[threadIdx.x] = off < 0 ? 0 : (int)pos;
+    }
+
+    // staging: piece id = thread + 512 j  ->  row id/8, 16-byte column id%8 (8 threads cover a row's 128 bytes).
+    // Rows past the last one re-read the last row; their accumulators are never stored.
+    const int s_col = (threadIdx.x & 7) * 8;
+    const int s_row = threadIdx.x >> 3;                            // + 64 j
+    const unsigned short* src_a[kAChunks];
+    const unsigned short* src_b[kBChunks];
+#pragma unroll
+    for (int j = 0; j < kAChunks; ++j) {
+        const int m = m0 + s_row + kStageRows * j;
+        src_a[j] = x + (size_t)(m < M ? m : M - 1) * a.hidden + k_begin + s_col;
+    }
+#pragma unroll
+    for (int j = 0; j < kBChunks; ++j) src_b[j] = w + (size_t)(s_row + kStageRows * j) * a.hidden + k_begin + s_col;
+    uintx4 ra[2][kAChunks], rb[2][kBChunks];                       // two steps of the tiles in flight
+
+    floatx4 acc[4][NT];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+#define KVS_FETCH(step, set)                                                                         \
+    _Pragma("unroll") for (int j = 0; j < kAChunks; ++j)                                             \
+        ra[set][j] = *reinterpret_cast<const uintx4*>(src_a[j] + (step) * kTileK);                   \
+    _Pragma("unroll") for (int j = 0; j < kBChunks; ++j)                                             \
+        rb[set][j] = *reinterpret_cast<const uintx4*>(src_b[j] + (step) * kTileK);
+#define KVS_STAGE(buf, set)                                                                          \
+    _Pragma("unroll") for (int j = 0; j < kAChunks; ++j)                                             \
+        *reinterpret_cast<uintx4*>(&sa[buf][s_row + kStageRows * j][s_col ^ ((s_row & 7) * 8)]) = ra[set][j]; \
+    _Pragma("unroll") for (int j = 0; j < kBChunks; ++j)                                             \
+        *reinterpret_cast<uintx4*>(&sb[buf][s_row + kStageRows * j][s_col ^ ((s_row & 7) * 8)]) = rb[set][j];
+#define KVS_READ(buf, kk, fa, fb)                                                                    \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
+        fa[i] = *reinterpret_cast<const bf16x8*>(&sa[buf][wm * 64 + i * 16 + l16][((kk) + quad * 8) ^ ((l16 & 7) * 8)]); \
+    _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                 \
+        const int col = (j < NT / 2 ? 0 : half) + wn * (D / 4) + (j % (NT / 2)) * 16 + l16;          \
+        fb[j] = *reinterpret_cast<const bf16x8*>(&sb[buf][col][((kk) + quad * 8) ^ ((l16 & 7) * 8)]); \
+    }
+#define KVS_MULTIPLY(fa, fb)                                                                         \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
+        _Pragma("unroll") for (int j = 0; j < NT; ++j)                                               \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    // Matrix instructions in fours, each four followed by two LDS reads: the order the scheduler
+    // is held to, so that operand reads travel under arithmetic instead of being waited for
+    // right where they are issued.
+#define KVS_FOURS_WITH_READS                                                                         \
+    if constexpr (NT == 4) {                                                                         \
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                              \
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0); /* matrix instructions */             \
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0); /* LDS reads */                       \
+        }                                                                                            \
+    }
+
+    // A step is two half-steps of 32 along the contraction, and the workgroup's barrier sits
+    // between them, not at the step's end.  Step s
+    //   - starts the global loads of the tiles of step s+2,
+    //   - multiplies its first half (operands already in registers) while it reads its second
+    //     half's operands from LDS buffer s%2,
+    //   - writes the tiles of step s+1 (loaded during step s-1) to the other buffer; barrier;
+    //   - multiplies its second half while it reads the first half's operands of step s+1.
+    // Every LDS read therefore has sixteen matrix instructions to hide behind, and nobody still
+    // reads the buffer being written: its last readers waited for their data before the barrier
+    // of the step before.  The number of steps is even; the last two steps re-load and re-stage
+    // the last tiles, which nobody uses, so that every step is the same straight-line code.
+#define KVS_STEP(step, set)                                                                          \
+    {                                                                                                \
+        const int ahead = (step) + 2 < n_steps ? (step) + 2 : n_steps - 1;                           \
+        KVS_FETCH(ahead, set)                                                                        \
+        KVS_READ(set, 32, fa1, fb1)                                                                  \
+        KVS_MULTIPLY(fa0, fb0)                                                                       \
+        KVS_STAGE(set ^ 1, set ^ 1)                                                                  \
+        if constexpr (NT == 4) __builtin_amdgcn_sched_group_barrier(0x020, kAChunks + kBChunks, 0);  \
+        KVS_FOURS_WITH_READS                                                                         \
+        __syncthreads();                                                                             \
+        KVS_READ(set ^ 1, 0, fa0, fb0)                                                               \
+        KVS_MULTIPLY(fa1, fb1)                                                                       \
+        KVS_FOURS_WITH_READS                                                                         \
+    }
+    bf16x8 fa0[4], fb0[NT], fa1[4], fb1[NT];
+    KVS_FETCH(0, 0)
+    KVS_STAGE(0, 0)
+    KVS_FETCH(1, 1)
+    __syncthreads();
+    KVS_READ(0, 0, fa0, fb0)
+    for (int step = 0; step < n_steps; step += 2) {
+        KVS_STEP(step, 0)
+        KVS_STEP(step + 1, 1)
+    }
+#undef KVS_STEP
+#undef KVS_FOURS_WITH_READS
+#undef KVS_READ
+#undef KVS_FETCH
+#undef KVS_STAGE
+#undef KVS_MULTIPLY
+
+    // lane holds, of tile (i, j), column l16 and rows 4*quad .. 4*quad+3
+    if (a.k_splits > 1) {
+        const size_t tile_id = (size_t)blockIdx.x * gridDim.y + blockIdx.y;
+        const size_t n_tiles = (size_t)gridDim.x * gridDim.y;
+        constexpr int kPairs = 4 * NT * 2;                         // 64-bit pieces of a thread's accumulators
+        unsigned long long* mine = reinterpret_cast<unsigned long long*>(a.partials) +
+                                   (blockIdx.z * n_tiles + tile_id) * (size_t)(kPairs * kTiledThreads) + threadIdx.x;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const floatx2 pv = {acc[i][j][2 * h], acc[i][j][2 * h + 1]};
+                    __hip_atomic_store(mine + (size_t)((i * NT + j) * 2 + h) * kTiledThreads,
+                                       __builtin_bit_cast(unsigned long long, pv), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
+        __shared__ int s_is_last;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0): the device-scope stores are acknowledged
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int arrived = atomicAdd(a.counters + tile_id, 1);
+            s_is_last = arrived == a.k_splits - 1;
+            if (s_is_last) atomicExch(a.counters + tile_id, 0);
+        }
+        __syncthreads();
+        if (!s_is_last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < a.k_splits; ++ks) {                  // split order: the sum does not depend on arrival
+            const unsigned long long* theirs = reinterpret_cast<const unsigned long long*>(a.partials) +
+                                               (ks * n_tiles + tile_id) * (size_t)(kPairs * kTiledThreads) + threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const floatx2 v2 = __builtin_bit_cast(
+                            floatx2, __hip_atomic_load(theirs + (size_t)((i * NT + j) * 2 + h) * kTiledThreads, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT));
+                        acc[i][j][2 * h] += v2[0];
+                        acc[i][j][2 * h + 1] += v2[1];
+                    }
+        }
+    }
+
+    const bool rotate = !is_v && a.rope_cos;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = wm * 64 + i * 16 + quad * 4 + r;
+            const long long off = row_page[row];                   // written before the first barrier
+            const int pos = row_pos[row];
+            unsigned short* page = static_cast<unsigned short*>(st.pool) + (off < 0 ? 0 : off);
+            const int t = pos % kPageTokens;
+#pragma unroll
+            for (int j = 0; j < NT / 2; ++j) {
+                const int c = wn * (D / 4) + j * 16 + l16;
+                float lo = acc[i][j][r], hi = acc[i][j + NT / 2][r];
+                if (rotate) {                                      // dropped rows read table row 0
+                    const float cs = a.rope_cos[(size_t)pos * half + c], sn = a.rope_sin[(size_t)pos * half + c];
+                    const float rl = lo * cs - hi * sn, rh = hi * cs + lo * sn;
+                    lo = rl;
+                    hi = rh;
+                }
+                if (off >= 0) {
+                    page[is_v ? v_index(t, c) : k_index(t, c)] = round_bf16(lo);
+                    page[is_v ? v_index(t, c + half) : k_index(t, c + half)] = round_bf16(hi);
+                }
+            }
+        }
+}
+
 }  // namespace
 
-// Workgroups per launch aimed at.  The contraction is split across workgroups only as far as
-// each wavefront keeps at least 128 elements of it.
+// Which kernel a call takes and how far its contraction is split across workgroups.
+namespace {
 constexpr long kTargetWorkgroups = 256;                  // one per compute unit measured fastest
-int project_k_splits(int Hkv, int head_dim, int hidden, int rows)
+constexpr int kTiledFromRows = 33;                       // more rows than this: the tiled kernel
+
+struct ProjectPlan {
+    bool tiled;
+    int k_splits;
+    size_t tiles;                // output tiles = arrival counters
+    size_t partial_bytes;        // per tile and split
+};
+
+ProjectPlan plan_project(int Hkv, int head_dim, int hidden, int rows)
 {
-    const long tiles = 2L * Hkv * (head_dim / 32) * ((rows + 15) / 16);
-    long want = (kTargetWorkgroups + tiles - 1) / tiles;
-    const long most = hidden / (kWaves * 128);
+    ProjectPlan p;
+    p.tiled = rows >= kTiledFromRows;
+    long most;                   // splits that leave every workgroup enough contraction
+    int unit;                    // the contraction of one split is a multiple of this
+    if (p.tiled) {
+        p.tiles = (size_t)2 * Hkv * ((rows + kTileRows - 1) / kTileRows);
+        p.partial_bytes = (size_t)kTiledThreads * 4 * (head_dim / 32) * 4 * sizeof(float);
+        most = hidden / 1024;
+        unit = 2 * kTileK;       // an even number of staged steps
+    } else {
+        p.tiles = (size_t)2 * Hkv * (head_dim / 32) * ((rows + 15) / 16);
+        p.partial_bytes = (size_t)kThreads * 2 * sizeof(float);
+        most = hidden / (kWaves * 128);
+        unit = kWaves * 32;      // every wavefront gets whole steps of 32
+    }
+    long want = (kTargetWorkgroups + (long)p.tiles - 1) / (long)p.tiles;
     want = want > most ? most : want;
     want = want < 1 ? 1 : want;
-    while (hidden % (kWaves * 32 * want) != 0) --want;    // every wavefront gets whole steps of 32
-    return (int)want;
+    while (hidden % (unit * want) != 0) --want;
+    p.k_splits = (int)want;
+    return p;
 }
+
+size_t counter_bytes(size_t tiles) { return (tiles * sizeof(int32_t) + 255) / 256 * 256; }
+}  // namespace
 
 size_t project_workspace_bytes(int Hkv, int head_dim, int hidden, int rows)
 {
-    const size_t tiles = (size_t)2 * Hkv * (head_dim / 32) * ((rows + 15) / 16);
-    const size_t counters = (tiles * sizeof(int32_t) + 255) / 256 * 256;
-    const int ks = project_k_splits(Hkv, head_dim, hidden, rows);
-    return counters + (ks > 1 ? (size_t)ks * tiles * kThreads * 2 * sizeof(float) : 0);
+    const ProjectPlan p = plan_project(Hkv, head_dim, hidden, rows);
+    return counter_bytes(p.tiles) + (p.k_splits > 1 ? (size_t)p.k_splits * p.tiles * p.partial_bytes : 0);
 }
 
 int launch_project_append(ProjectArgs a, void* workspace, void* stream)
 {
-    const int tiles_per_head = a.st.head_dim / 32;
-    const unsigned col_wgs = 2u * a.st.Hkv * tiles_per_head;
-    const unsigned row_wgs = (unsigned)((a.B * a.T + 15) / 16);
-    a.k_splits = project_k_splits(a.st.Hkv, a.st.head_dim, a.hidden, a.B * a.T);
-    const size_t tiles = (size_t)col_wgs * row_wgs;
+    const int rows = a.B * a.T;
+    const ProjectPlan p = plan_project(a.st.Hkv, a.st.head_dim, a.hidden, rows);
+    a.k_splits = p.k_splits;
     a.counters = static_cast<int32_t*>(workspace);
-    a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + (tiles * sizeof(int32_t) + 255) / 256 * 256);
-    hipLaunchKernelGGL(project_append_bf16_kernel, dim3(col_wgs, row_wgs, a.k_splits), dim3(kThreads), 0,
-                       static_cast<hipStream_t>(stream), a);
+    a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(p.tiles));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (p.tiled) {
+        const dim3 grid(2u * a.st.Hkv, (unsigned)((rows + kTileRows - 1) / kTileRows), p.k_splits);
+        if (a.st.head_dim == 128)
+            hipLaunchKernelGGL(project_append_tiled_kernel<128>, grid, dim3(kTiledThreads), 0, s, a);
+        else
+            hipLaunchKernelGGL(project_append_tiled_kernel<64>, grid, dim3(kTiledThreads), 0, s, a);
+    } else {
+        const dim3 grid(2u * a.st.Hkv * (a.st.head_dim / 32), (unsigned)((rows + 15) / 16), p.k_splits);
+        hipLaunchKernelGGL(project_append_bf16_kernel, grid, dim3(kThreads), 0, s, a);
+    }
     return (int)hipGetLastError();
 }
 

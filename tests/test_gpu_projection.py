@@ -32,12 +32,16 @@ def _bf16_round(a):
     return torch.from_numpy(np.asarray(a, np.float32)).to(torch.bfloat16)
 
 
-# The last four shapes split the contraction over 4, 4, 3 and 8 workgroups per output tile (the
-# merge path); the first four finish inside one workgroup.
+# Up to 32 rows take the streaming kernel, more the tiled one.  Shapes 5-8 split the streaming
+# kernel's contraction over 4, 4, 3 and 8 workgroups per output tile (the merge path), shapes 9-11
+# the tiled kernel's over 2, 4 and 2 (head sizes 128 and 64, one and several row tiles with a
+# ragged last one); the others finish inside one workgroup.
 @pytest.mark.parametrize("Hq,Hkv,d,hidden,B,T_new,rope", [(8, 2, 128, 512, 3, 1, True), (4, 4, 64, 256, 2, 21, True),
                                                             (8, 8, 128, 1024, 5, 64, True), (4, 1, 128, 128, 4, 5, False),
                                                             (32, 8, 128, 4096, 4, 1, True), (8, 2, 128, 2048, 3, 1, True),
-                                                            (8, 2, 128, 1536, 2, 17, True), (8, 1, 64, 4096, 2, 1, False)])
+                                                            (8, 2, 128, 1536, 2, 16, True), (8, 1, 64, 4096, 2, 1, False),
+                                                            (8, 2, 128, 2048, 2, 40, True), (8, 2, 64, 4096, 3, 50, True),
+                                                            (4, 1, 128, 2048, 5, 60, False), (8, 2, 128, 1536, 2, 17, True)])
 def test_project_append_parity(kb, Hq, Hkv, d, hidden, B, T_new, rope):
     L, cap = 3, 160
     share = np.array([0, 1, 1], np.int32)

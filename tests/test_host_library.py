@@ -98,7 +98,9 @@ def test_store_and_workspace_sizes():
     big = _desc(Hq=32, Hkv=8)
     assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 4, 1) == 256 + 4 * 64 * 256 * 8
     assert lib.kvs_project_workspace_bytes(C.byref(big), 128, 4, 1) == 256          # nothing to split
-    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 64, 64) == 64 * 256 * 4   # enough tiles already
+    # more than 32 rows: 256-row tiles of a whole head, 512 threads x 64 accumulators per tile and split
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 64, 64) == 2 * 8 * 16 * 4      # enough tiles already
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 16, 64) == 256 + 4 * 64 * 512 * 64 * 4
     assert lib.kvs_project_workspace_bytes(C.byref(big), 100, 4, 1) == 0
     assert lib.kvs_project_workspace_bytes(C.byref(_desc(dtype=kb.KVS_F32)), 4096, 4, 1) == 0
 
