@@ -80,6 +80,8 @@ typedef int (*kvs_accept_fn)(const int32_t* candidate_share_map, int L, void* us
  *   share_map, slot_of_layer   host, out[L];  n_slots, n_shared   host, out
  * Returns KVS_OK, or KVS_ERR_TARGET_UNREACHED with the partial strategy in the outputs
  * when the ranking is exhausted first (the paper's "return None").
+ * The random-sharing baseline (Sec. 5.2, random pairs at a fixed compression rate) is the same
+ * walk over a ranking drawn at random: pass a matrix of independent random values, accept = NULL.
  */
 int kvs_build_share_map(const float* dist, int L, int target_shared, int order,
                         kvs_accept_fn accept, void* user,

@@ -40,6 +40,21 @@ def test_share_map_matches_oracle_bitwise(L, C_, order):
     assert s2.tolist() == oslot and n2 == on_slots
 
 
+def test_random_sharing_baseline_is_the_walk_over_a_random_ranking():
+    """Sec. 5.2 compares against randomly chosen pairs at 25 % compression, three draws: a matrix of
+    random values and no similarity test gives such a strategy, valid and different per draw."""
+    L, C_ = 40, 10
+    maps = []
+    for seed in range(3):
+        D = np.random.default_rng(seed).random((L, L)).astype(np.float32)
+        st, share, slot, n_slots, n_shared = kb.kvs_build_share_map(D, C_, 0)
+        assert st == kb.KVS_OK and n_shared == C_ and n_slots == L - C_
+        assert kb.kvs_validate_share_map(share) == kb.KVS_OK
+        assert share.tolist() == osm.build_share_map(D, L, C_)[1]
+        maps.append(tuple(share.tolist()))
+    assert len(set(maps)) == 3
+
+
 def test_share_map_accept_callback_and_unreachable_target():
     D = np.array([[0, 1, 7, 8], [1, 0, 6, 9], [7, 6, 0, 5], [8, 9, 5, 0]], np.float32)
     calls = []
