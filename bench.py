@@ -194,6 +194,73 @@ def bench_project(args, torch, kb, inputs, dev):
         "roofline": roof}))
 
 
+def bench_sparse(args, torch, kb, inputs, dev):
+    """Decode attention over intra-layer sparsified slots, Llama-3-8B 32k shape: every (sequence,
+    kv head) keeps a random 80 % of its 32768 tokens (the paper's "additional 20 %" on top of layer
+    sharing), compacted in place by kvs_compact_kv; a step = one kvs_decode_attention_per_head
+    launch per layer.  The compaction is timed separately (a maintenance operation)."""
+    w = inputs.WORKLOADS["llama3-8b-32k"]
+    n_layers = 4
+    mb = w.max_blocks_per_seq
+    table = inputs.make_block_table(w.B, mb, w.B * mb, 1)
+    store = kb.KVStore(np.arange(n_layers, dtype=np.int32), w.Hq, w.Hkv, w.d, "bf16", w.B * mb, mb, block_table=table)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_BASE)
+    rng = np.random.default_rng(inputs.SEED_BASE)
+    zeros = torch.zeros(w.B, dtype=torch.int32, device=dev)
+    n_keep = int(0.8 * w.context)
+    kv_lens = np.full((n_layers, w.B, w.Hkv), n_keep, np.int32)
+    host0 = keep0 = None
+    compact_ms = []
+    for l in range(n_layers):
+        k = torch.randn((w.B, w.context, w.Hkv, w.d), device=dev, generator=gen).bfloat16()
+        v = torch.randn((w.B, w.context, w.Hkv, w.d), device=dev, generator=gen).bfloat16()
+        assert kb.kvs_append_kv(store, l, k, v, zeros) == kb.KVS_OK
+        idx = np.stack([np.stack([np.sort(rng.choice(w.context, size=n_keep, replace=False)) for _ in range(w.Hkv)])
+                        for _ in range(w.B)]).astype(np.int32)
+        if l == 0:
+            host0, keep0 = (k.cpu(), v.cpu()), idx
+        idx_d, cnt_d = torch.from_numpy(idx).to(dev), torch.from_numpy(kv_lens[l]).to(dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        assert kb.kvs_compact_kv(store, l, idx_d, cnt_d) == kb.KVS_OK
+        e1.record()
+        torch.cuda.synchronize()
+        compact_ms.append(e0.elapsed_time(e1))
+        del k, v
+    q = [torch.randn((w.B, w.Hq, w.d), device=dev, generator=gen).bfloat16() for _ in range(n_layers)]
+    lens_d = torch.from_numpy(kv_lens).to(dev)
+    out = torch.empty((n_layers, w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    ws = store.workspace(w.B, 1)
+
+    def one_round():
+        for l in range(n_layers):
+            kb.kvs_decode_attention_per_head(store, l, q[l], lens_d, out=out[l], workspace=ws)
+
+    us = _event_time_us(torch, lambda: [one_round() for _ in range(8)], args.steps, args.warmup) / (8 * n_layers)
+    nbytes = int(kv_lens[0].sum()) * w.d * 2 * 2 + w.B * w.Hq * w.d * (2 + 4)
+    achieved = nbytes / us / 1e3
+    line = {
+        "metric": "decode attention over sparsified shared-KV slots, tokens/s per layer",
+        "value": round(w.B / (us * 1e-6), 1), "unit": "tokens/s per layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(us * 1e-3, 5), "higher_is_better": True, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "llama3-8b-32k, 80 % of the tokens kept per kv head", "batch": w.B, "q_heads": w.Hq,
+                   "kv_heads": w.Hkv, "head_dim": w.d, "context": w.context, "kept_per_head": n_keep},
+        "compact_ms_per_layer": round(float(np.mean(compact_ms)), 3),
+        "roofline": {"bound": "hbm", "kernel": "attn_bf16_kernel<128,1> (per-head lengths)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "launch_us": round(us, 2), "algorithmic_bytes": nbytes}}
+    if not args.no_cpu_baseline:
+        from oracle.sparse import sparse_decode_attention
+        want = sparse_decode_attention(inputs.to_oracle_array(q[0].cpu()), inputs.to_oracle_array(host0[0]),
+                                       inputs.to_oracle_array(host0[1]), keep0)
+        got = out[0].cpu().numpy().astype(np.float64)
+        err = np.sqrt(((got - want) ** 2).sum(-1)) / np.sqrt((want ** 2).sum(-1))
+        line["parity_rel_l2_max"] = float(err.max())
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -204,10 +271,11 @@ def main():
     ap.add_argument("--split-tokens", type=int, default=0)
     ap.add_argument("--project-rows", type=int, default=1,
                     help="--mode project: new rows per sequence (1 = decode step, more = prefill chunk)")
-    ap.add_argument("--mode", choices=["decode", "prefill", "distance", "project"], default="decode",
+    ap.add_argument("--mode", choices=["decode", "prefill", "distance", "project", "sparse"], default="decode",
                     help="decode (default): the whole decode step, the headline metric.  prefill: the 64-row "
                          "causal chunk of the llama2-13b workload.  distance: the 48-layer calibration matrix. "
-                         "The last two time the other kernels of the path, one JSON line each.")
+                         "project: the fused K/V projection (see --project-rows).  sparse: decode attention over "
+                         "sparsified slots.  All but decode time the other kernels of the path, one JSON line each.")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (torch) so that a counter trace of this "
                          "command contains a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -229,6 +297,8 @@ def main():
         return bench_distance(args, torch, kb, inputs, dev)
     if args.mode == "project":
         return bench_project(args, torch, kb, inputs, dev)
+    if args.mode == "sparse":
+        return bench_sparse(args, torch, kb, inputs, dev)
     w = inputs.WORKLOADS[args.workload]
 
     share = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)

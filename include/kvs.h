@@ -195,6 +195,52 @@ int kvs_prefill_attention(const kvs_store* store, int layer, const void* q,
                           const int32_t* start_pos, int B, int T_new, float* out,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------- intra-layer sparsified slots (per-head token sets)
+ *
+ * Layer sharing composes with token-dropping methods such as H2O and PyramidInfer (Sec. 4.6,
+ * "Compatibility with Intra-layer Compression", and the appendix on their reproduction): every
+ * layer that keeps a cache sparsifies it by that method's own rule, and a layer that shares
+ * reads the already sparsified cache of its donor.  Which tokens to keep is the caller's
+ * policy; the three calls below are the storage and attention side.  A sparsified slot holds,
+ * for every (sequence, kv head), its kept tokens at positions 0 .. n-1 of the head's pages, n
+ * differing per head; the attention is the softmax over exactly those tokens and does not
+ * depend on their order (positions are already inside the keys).
+ */
+
+/*
+ * Keep, for every (sequence, kv head) of the slot `layer` owns, the tokens at positions
+ * keep_idx[b][g][0 .. keep_count[b][g]) and move them to positions 0 .. keep_count[b][g], in
+ * place.  keep_idx must be strictly increasing within a head and below the head's current
+ * length (not checked: other values stay inside the store but give an unspecified token
+ * set); counts are clamped to [0, max_keep].  Positions at and after the count keep stale data.
+ *   keep_idx device int32 [B][Hkv][max_keep];  keep_count device int32 [B][Hkv].
+ * Returns KVS_NOOP for a layer that reads a donor's cache (the donor's compaction is the one
+ * it sees).  Cost: the workgroups of a (sequence, kv head) walk its kept tokens in order, 128
+ * at a time; a maintenance operation, not part of the decode step.
+ */
+int kvs_compact_kv(const kvs_store* store, int layer, const int32_t* keep_idx,
+                   const int32_t* keep_count, int max_keep, int B, void* stream);
+
+/*
+ * kvs_append_kv with a write position per (sequence, kv head): rows i of head g of sequence b go
+ * to positions pos[b][g] + i.  With per-head lengths this is both "extend the head by one
+ * token" (pos = its length) and "overwrite the token the policy just evicted" (pos = its
+ * index).  pos device int32 [B][Hkv]; everything else as kvs_append_kv.
+ */
+int kvs_append_kv_per_head(const kvs_store* store, int layer, const void* k_new, const void* v_new,
+                           const int32_t* pos, int B, int T_new, void* stream);
+
+/*
+ * kvs_decode_attention over a sparsified slot: kv head g of sequence b attends to its first
+ * kv_lens[slot][b][g] tokens, slot = slot_of_layer[share_map[layer]] (taken from the store's
+ * host copies of the maps; pages are still resolved on the device).  A length of 0 gives zero
+ * rows for the head's query heads; lengths above the capacity are clamped.
+ *   kv_lens device int32 [n_slots][B][Hkv];  everything else as kvs_decode_attention.
+ */
+int kvs_decode_attention_per_head(const kvs_store* store, int layer, const void* q,
+                                  const int32_t* kv_lens, int B, float* out,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
 /* Context tokens handled by one workgroup of the split-context decode kernel; 0 restores the
  * built-in choice.  Must be a multiple of 64.  Process-wide; for tuning and tests. */
 int kvs_set_split_tokens(int tokens);

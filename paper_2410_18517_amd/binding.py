@@ -25,6 +25,7 @@ EXPORTS = [
     "kvs_decode_attention", "kvs_prefill_attention", "kvs_set_split_tokens",
     "kvs_layer_distance", "kvs_distance_workspace_bytes", "kvs_avg_cos_sim", "kvs_cos_sim_workspace_bytes",
     "kvs_project_append_kv", "kvs_project_workspace_bytes",
+    "kvs_compact_kv", "kvs_append_kv_per_head", "kvs_decode_attention_per_head",
 ]
 
 
@@ -71,10 +72,13 @@ def lib():
         L.kvs_slots_from_share_map.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.kvs_append_kv.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_int, C.c_int, C.c_void_p]
+        L.kvs_append_kv_per_head.argtypes = L.kvs_append_kv.argtypes
+        L.kvs_compact_kv.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         L.kvs_gather_kv.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_int, C.c_int, C.c_int,
                                     C.c_void_p, C.c_void_p, C.c_void_p]
         L.kvs_decode_attention.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.kvs_decode_attention_per_head.argtypes = L.kvs_decode_attention.argtypes
         L.kvs_prefill_attention.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                             C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvs_set_split_tokens.argtypes = [C.c_int]
@@ -216,6 +220,28 @@ def kvs_append_kv(store: KVStore, layer, k_new, v_new, start_pos) -> int:
                                       sp.data_ptr(), B, T_new, _stream()), ok=(KVS_OK, KVS_NOOP))
 
 
+def kvs_append_kv_per_head(store: KVStore, layer, k_new, v_new, pos) -> int:
+    """As kvs_append_kv with a write position per (sequence, kv head): pos device/host int32 [B, Hkv]."""
+    assert k_new.is_cuda and k_new.is_contiguous() and v_new.is_contiguous()
+    assert k_new.dtype == store.torch_dtype and v_new.dtype == store.torch_dtype
+    B, T_new = k_new.shape[:2]
+    assert tuple(k_new.shape) == (B, T_new, store.desc.Hkv, store.desc.head_dim) == tuple(v_new.shape)
+    sp = _dev_i32(pos, store.device)
+    assert sp.numel() == B * store.desc.Hkv
+    return _check(lib().kvs_append_kv_per_head(C.byref(store.c), int(layer), k_new.data_ptr(), v_new.data_ptr(),
+                                               sp.data_ptr(), B, T_new, _stream()), ok=(KVS_OK, KVS_NOOP))
+
+
+def kvs_compact_kv(store: KVStore, layer, keep_idx, keep_count) -> int:
+    """keep_idx: int32 [B, Hkv, max_keep] increasing positions; keep_count: int32 [B, Hkv]."""
+    idx = _dev_i32(keep_idx, store.device)
+    cnt = _dev_i32(keep_count, store.device)
+    B, Hkv, max_keep = idx.shape
+    assert Hkv == store.desc.Hkv and tuple(cnt.shape) == (B, Hkv)
+    return _check(lib().kvs_compact_kv(C.byref(store.c), int(layer), idx.data_ptr(), cnt.data_ptr(),
+                                       int(max_keep), int(B), _stream()), ok=(KVS_OK, KVS_NOOP))
+
+
 def kvs_project_append_kv(store: KVStore, layer, x, w_k, w_v, start_pos, rope_cos=None, rope_sin=None,
                           workspace=None) -> int:
     """x: device bf16 [B, T_new, hidden]; w_k, w_v: device bf16 [Hkv*d, hidden]; rope tables device fp32
@@ -269,6 +295,21 @@ def kvs_decode_attention(store: KVStore, layer, q, seq_lens, out=None, workspace
     ws = workspace if workspace is not None else store.workspace(B, 1)
     _check(lib().kvs_decode_attention(C.byref(store.c), int(layer), q.data_ptr(), sl.data_ptr(), B,
                                       out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def kvs_decode_attention_per_head(store: KVStore, layer, q, kv_lens, out=None, workspace=None):
+    """As kvs_decode_attention over a sparsified slot: kv_lens int32 [n_slots, B, Hkv]."""
+    assert q.is_cuda and q.is_contiguous() and q.dtype == store.torch_dtype
+    B = q.shape[0]
+    assert tuple(q.shape) == (B, store.desc.Hq, store.desc.head_dim)
+    kl = _dev_i32(kv_lens, store.device)
+    assert tuple(kl.shape) == (store.desc.n_slots, B, store.desc.Hkv)
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=store.device)
+    ws = workspace if workspace is not None else store.workspace(B, 1)
+    _check(lib().kvs_decode_attention_per_head(C.byref(store.c), int(layer), q.data_ptr(), kl.data_ptr(), B,
+                                               out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
     return out
 
 

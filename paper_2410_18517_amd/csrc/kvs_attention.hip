@@ -78,7 +78,7 @@ __global__ void copy_rows_kernel(CopyArgs a)
     const int g = (int)((tid / chunks) % st.Hkv);
     const int i = (int)((tid / ((long)chunks * st.Hkv)) % a.T);
     const int b = (int)(tid / ((long)chunks * st.Hkv * a.T));
-    const long pos = (long)(a.start_pos ? a.start_pos[b] : a.t0) + i;
+    const long pos = (long)(a.start_pos ? a.start_pos[a.pos_per_head ? b * st.Hkv + g : b] : a.t0) + i;
     if (pos < 0 || pos >= (long)st.max_blocks_per_seq * kPageTokens) return;
     const int slot = resolve_slot(st);
     const int blk = block_of(st, b, (int)(pos / kPageTokens));
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void append_pages_bf16_kernel(CopyArgs a)
     const StoreView& st = a.st;
     const int D = st.head_dim;                    // 64 or 128
     const int g = blockIdx.y, b = blockIdx.z;
-    const long start = a.start_pos[b];
+    const long start = a.start_pos[a.pos_per_head ? b * st.Hkv + g : b];
     const long cap = (long)st.max_blocks_per_seq * kPageTokens;
     if (start < 0 || start >= cap) return;
     const long end = start + a.T < cap ? start + a.T : cap;
@@ -182,6 +182,73 @@ __global__ __launch_bounds__(256) void append_pages_bf16_kernel(CopyArgs a)
     }
 }
 
+// In-place compaction of a slot after token eviction: for every (sequence, kv head) the tokens
+// at the increasing positions keep_idx[0 .. count) move to positions 0 .. count.  A workgroup
+// owns one (kv head, sequence) and two of the 16-byte channel pieces of its rows (pieces never
+// interact, so they spread over workgroups) and walks the destination in chunks of 128 tokens:
+// thread (t, piece) loads its piece of K and of V of source token keep_idx[chunk + t], the
+// workgroup meets at a barrier, then the pieces are stored at chunk + t.  Because
+// keep_idx[j] >= j, a chunk reads only positions at or behind its own start and writes only its
+// own 128 positions, so chunks never touch each other's data and one barrier per chunk is enough.
+constexpr int kCompactTokens = 128;
+template <bool kBf16>
+__global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
+{
+    const StoreView& st = a.st;
+    const int D = st.head_dim;
+    constexpr int per = kBf16 ? 8 : 4;
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int ch = blockIdx.z * 2 + (threadIdx.x & 1);         // this thread's piece of the row
+    const int tt = threadIdx.x >> 1;
+    const int cap = st.max_blocks_per_seq * kPageTokens;
+    int count = a.keep_count[b * st.Hkv + g];
+    const int most = a.max_keep < cap ? a.max_keep : cap;
+    count = count < 0 ? 0 : (count > most ? most : count);
+    const int32_t* idx = a.keep_idx + ((size_t)b * st.Hkv + g) * a.max_keep;
+    const int slot = resolve_slot(st);
+    for (int c0 = 0; c0 < count; c0 += kCompactTokens) {
+        const int j = c0 + tt;
+        const bool active = j < count && ch * per < D;
+        int src = active ? idx[j] : 0;
+        src = src < 0 ? 0 : (src >= cap ? cap - 1 : src);
+        const int sblk = block_of(st, b, src / kPageTokens);
+        const int dblk = block_of(st, b, (j < cap ? j : cap - 1) / kPageTokens);
+        const bool ok = active && sblk >= 0 && sblk < st.num_blocks && dblk >= 0 && dblk < st.num_blocks;
+        const int ts = src % kPageTokens, td = j % kPageTokens;
+        uint4 kreg = make_uint4(0, 0, 0, 0), vreg = make_uint4(0, 0, 0, 0);
+        if (ok) {
+            if (kBf16) {
+                const unsigned short* kp = static_cast<const unsigned short*>(st.pool) + page_offset(st, slot, sblk, g);
+                const unsigned short* vp = kp + kPageTokens * D;
+                kreg = *reinterpret_cast<const uint4*>(kp + k_index_bf16(ts, ch * 8));
+                unsigned w[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[e >> 1] |= (unsigned)vp[v_index_bf16(ts, ch * 8 + e)] << ((e & 1) * 16);
+                vreg = make_uint4(w[0], w[1], w[2], w[3]);
+            } else {
+                const float* kp = static_cast<const float*>(st.pool) + page_offset(st, slot, sblk, g) + (size_t)ts * D + ch * 4;
+                kreg = *reinterpret_cast<const uint4*>(kp);
+                vreg = *reinterpret_cast<const uint4*>(kp + kPageTokens * D);
+            }
+        }
+        __syncthreads();
+        if (ok) {
+            if (kBf16) {
+                unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, slot, dblk, g);
+                unsigned short* vp = kp + kPageTokens * D;
+                *reinterpret_cast<uint4*>(kp + k_index_bf16(td, ch * 8)) = kreg;
+                const unsigned w[4] = {vreg.x, vreg.y, vreg.z, vreg.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vp[v_index_bf16(td, ch * 8 + e)] = (unsigned short)(w[e >> 1] >> ((e & 1) * 16));
+            } else {
+                float* kp = static_cast<float*>(st.pool) + page_offset(st, slot, dblk, g) + (size_t)td * D + ch * 4;
+                *reinterpret_cast<uint4*>(kp) = kreg;
+                *reinterpret_cast<uint4*>(kp + kPageTokens * D) = vreg;
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ fp32 store
 // One wavefront per (sequence, query row, query head); the whole context in one pass.
 // Lanes own tokens for the scores and channels for the weighted sum.
@@ -207,7 +274,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a)
     const int group = st.Hq / st.Hkv;
     const int g = h / group;
     const long cap = (long)st.max_blocks_per_seq * kPageTokens;
-    long n = (long)a.lens[b] + a.lens_bias + r;
+    long n = (long)a.lens[a.lens_per_head ? b * st.Hkv + g : b] + a.lens_bias + r;
     n = n < 0 ? 0 : (n > cap ? cap : n);
     const size_t row = (((size_t)b * a.T_new + r) * st.Hq + h) * D;
     __shared__ float qs[256];
@@ -382,7 +449,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
         first_page[j] = pg < st.max_blocks_per_seq ? pg : st.max_blocks_per_seq - 1;
     }
     const int32_t* look = nullptr;
-    if (lane == 0) look = a.lens + b;
+    if (lane == 0) look = a.lens + (a.lens_per_head ? b * st.Hkv + g : b);
     else if (lane == 1) look = st.share_map + st.layer;
     else if (lane < 8) {
         int pg = first_page[0];
@@ -695,6 +762,17 @@ int launch_append(const CopyArgs& a, void* stream)
     const long total = (long)a.B * a.T * a.st.Hkv * (a.st.head_dim / per);
     const unsigned blocks = (unsigned)((total + 255) / 256);
     hipLaunchKernelGGL(copy_rows_kernel<true>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    return (int)hipGetLastError();
+}
+
+int launch_compact(const CompactArgs& a, void* stream)
+{
+    const int pieces = a.st.head_dim / (a.st.dtype == 1 ? 8 : 4);
+    const dim3 grid(a.st.Hkv, a.B, (pieces + 1) / 2);
+    if (a.st.dtype == 1)
+        hipLaunchKernelGGL(compact_kernel<true>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    else
+        hipLaunchKernelGGL(compact_kernel<false>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
     return (int)hipGetLastError();
 }
 

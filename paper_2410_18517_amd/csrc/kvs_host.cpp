@@ -266,8 +266,8 @@ size_t kvs_workspace_bytes(const kvs_desc* d, int B, int max_q_rows)
     return need;
 }
 
-int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const void* v_new,
-                  const int32_t* start_pos, int B, int T_new, void* stream)
+static int append_common(const kvs_store* store, int layer, const void* k_new, const void* v_new,
+                         const int32_t* start_pos, int pos_per_head, int B, int T_new, void* stream)
 {
     if (int rc = check_store(store, layer)) return rc;
     if (!k_new || !v_new || !start_pos) return fail(KVS_ERR_INVALID_ARG, "k_new, v_new or start_pos is NULL");
@@ -284,10 +284,46 @@ int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const vo
     a.k = const_cast<void*>(k_new);
     a.v = const_cast<void*>(v_new);
     a.start_pos = start_pos;
+    a.pos_per_head = pos_per_head;
     a.t0 = 0;
     a.B = B;
     a.T = T_new;
     if (int e = kvs::launch_append(a, stream)) return fail(KVS_ERR_HIP, "append launch: %s", kvs::hip_error_string(e));
+    return KVS_OK;
+}
+
+int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const void* v_new,
+                  const int32_t* start_pos, int B, int T_new, void* stream)
+{
+    return append_common(store, layer, k_new, v_new, start_pos, 0, B, T_new, stream);
+}
+
+int kvs_append_kv_per_head(const kvs_store* store, int layer, const void* k_new, const void* v_new,
+                           const int32_t* pos, int B, int T_new, void* stream)
+{
+    return append_common(store, layer, k_new, v_new, pos, 1, B, T_new, stream);
+}
+
+int kvs_compact_kv(const kvs_store* store, int layer, const int32_t* keep_idx, const int32_t* keep_count,
+                   int max_keep, int B, void* stream)
+{
+    if (int rc = check_store(store, layer)) return rc;
+    if (!keep_idx || !keep_count) return fail(KVS_ERR_INVALID_ARG, "keep_idx or keep_count is NULL");
+    if (B <= 0 || max_keep <= 0) return fail(KVS_ERR_INVALID_ARG, "B and max_keep must be positive (B=%d, max_keep=%d)", B, max_keep);
+    if (max_keep > store->desc.max_blocks_per_seq * KVS_BLOCK_TOKENS)
+        return fail(KVS_ERR_CAPACITY, "max_keep=%d exceeds the per-sequence capacity %d", max_keep,
+                    store->desc.max_blocks_per_seq * KVS_BLOCK_TOKENS);
+    if (!store->block_table && (long)B * store->desc.max_blocks_per_seq > store->desc.num_blocks)
+        return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
+    if (B > 65535) return fail(KVS_ERR_CAPACITY, "B is limited to 65535");
+    if (store->host_share_map[layer] != layer) return KVS_NOOP;   // its donor's compaction is the one it reads
+    kvs::CompactArgs a;
+    a.st = view_of(store, layer);
+    a.keep_idx = keep_idx;
+    a.keep_count = keep_count;
+    a.max_keep = max_keep;
+    a.B = B;
+    if (int e = kvs::launch_compact(a, stream)) return fail(KVS_ERR_HIP, "compaction launch: %s", kvs::hip_error_string(e));
     return KVS_OK;
 }
 
@@ -355,6 +391,7 @@ int kvs_gather_kv(const kvs_store* store, int layer, int t0, int T, int B,
     a.k = k_out;
     a.v = v_out;
     a.start_pos = nullptr;
+    a.pos_per_head = 0;
     a.t0 = t0;
     a.B = B;
     a.T = T;
@@ -363,7 +400,7 @@ int kvs_gather_kv(const kvs_store* store, int layer, int t0, int T, int B,
 }
 
 static int attention_common(const kvs_store* store, int layer, const void* q, const int32_t* lens,
-                            int lens_bias, int B, int T_new, float* out, void* workspace,
+                            int lens_per_head, int lens_bias, int B, int T_new, float* out, void* workspace,
                             size_t workspace_bytes, void* stream)
 {
     if (int rc = check_store(store, layer)) return rc;
@@ -384,6 +421,7 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     a.st = view_of(store, layer);
     a.q = q;
     a.lens = lens;
+    a.lens_per_head = lens_per_head;
     a.lens_bias = lens_bias;
     a.B = B;
     a.T_new = T_new;
@@ -399,14 +437,27 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
 int kvs_decode_attention(const kvs_store* store, int layer, const void* q, const int32_t* seq_lens,
                          int B, float* out, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return attention_common(store, layer, q, seq_lens, 0, B, 1, out, workspace, workspace_bytes, stream);
+    return attention_common(store, layer, q, seq_lens, 0, 0, B, 1, out, workspace, workspace_bytes, stream);
+}
+
+int kvs_decode_attention_per_head(const kvs_store* store, int layer, const void* q, const int32_t* kv_lens,
+                                  int B, float* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (int rc = check_store(store, layer)) return rc;
+    if (!kv_lens) return fail(KVS_ERR_INVALID_ARG, "kv_lens is NULL");
+    if (B <= 0) return fail(KVS_ERR_INVALID_ARG, "B must be positive (B=%d)", B);
+    // the lengths of the slot this layer reads: its donor's (the host copies of the two maps
+    // mirror the device ones the kernel resolves the pages with)
+    const int slot = store->host_slot_of_layer[store->host_share_map[layer]];
+    const int32_t* lens = kv_lens + (size_t)slot * B * store->desc.Hkv;
+    return attention_common(store, layer, q, lens, 1, 0, B, 1, out, workspace, workspace_bytes, stream);
 }
 
 int kvs_prefill_attention(const kvs_store* store, int layer, const void* q, const int32_t* start_pos,
                           int B, int T_new, float* out, void* workspace, size_t workspace_bytes,
                           void* stream)
 {
-    return attention_common(store, layer, q, start_pos, 1, B, T_new, out, workspace, workspace_bytes, stream);
+    return attention_common(store, layer, q, start_pos, 0, 1, B, T_new, out, workspace, workspace_bytes, stream);
 }
 
 size_t kvs_distance_workspace_bytes(int L)

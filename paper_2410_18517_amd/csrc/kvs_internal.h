@@ -18,6 +18,7 @@ struct AttnArgs {
     StoreView st;
     const void* q;          // device [B][T_new][Hq][D], store dtype
     const int32_t* lens;    // device [B]: decode: tokens in the cache; prefill: position of row 0
+    int32_t lens_per_head;  // 1: lens is [B][Hkv], the tokens each kv head of the slot still holds (decode only)
     int32_t lens_bias;      // 0 for decode (row r sees lens + r keys), 1 for prefill
     int32_t B, T_new;
     float* out;             // device fp32 [B][T_new][Hq][D]
@@ -31,7 +32,15 @@ struct CopyArgs {
     void* k;                // device [B][T][Hkv][D]
     void* v;
     const int32_t* start_pos;  // device [B] (append) or nullptr (gather: t0 for all)
+    int32_t pos_per_head;      // 1: start_pos is [B][Hkv]
     int32_t t0, B, T;
+};
+
+struct CompactArgs {
+    StoreView st;
+    const int32_t* keep_idx;    // device [B][Hkv][max_keep], increasing token positions
+    const int32_t* keep_count;  // device [B][Hkv]
+    int32_t max_keep, B;
 };
 
 struct ProjectArgs {
@@ -51,6 +60,7 @@ struct ProjectArgs {
 // Each returns hipError_t as int (0 = success) after enqueueing on `stream`.
 int launch_append(const CopyArgs& a, void* stream);
 int launch_gather(const CopyArgs& a, void* stream);
+int launch_compact(const CompactArgs& a, void* stream);
 int launch_attention(const AttnArgs& a, void* stream);
 int launch_project_append(ProjectArgs a, void* workspace, void* stream);
 size_t project_workspace_bytes(int Hkv, int head_dim, int hidden, int rows);

@@ -1,0 +1,166 @@
+"""GPU parity of the sparsified-slot calls (per-head kept-token sets) against the oracle.
+
+Compaction and per-head appends move bit patterns: compared bit-exactly through kvs_gather_kv.
+Attention over the kept sets: the oracle works on the uncompacted cache and the keep lists
+themselves, so a wrong move, a wrong length table row or a wrong slot all show up; tolerance as
+for the dense attention.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle.sparse import sparse_decode_attention, compact
+from paper_2410_18517_amd import inputs
+from helpers import Case, rel_l2_rows, REL_L2_ATTENTION
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kb():
+    from paper_2410_18517_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return binding
+
+
+def _keep_lists(rng, B, Hkv, n_tokens, lo, hi):
+    """keep[b][h]: a sorted random subset of the first n_tokens[b] tokens, lo..hi of them kept."""
+    keep = []
+    for b in range(B):
+        row = []
+        for h in range(Hkv):
+            frac = rng.uniform(lo, hi)
+            n = max(1, int(round(frac * n_tokens[b])))
+            row.append(np.sort(rng.choice(n_tokens[b], size=n, replace=False)).astype(np.int32))
+        keep.append(row)
+    return keep
+
+
+def _pack(keep, B, Hkv):
+    max_keep = max(len(s) for row in keep for s in row)
+    idx = np.zeros((B, Hkv, max_keep), np.int32)
+    cnt = np.zeros((B, Hkv), np.int32)
+    for b in range(B):
+        for h in range(Hkv):
+            idx[b, h, :len(keep[b][h])] = keep[b][h]
+            cnt[b, h] = len(keep[b][h])
+    return idx, cnt
+
+
+@pytest.mark.parametrize("dtype,d,Hq,Hkv,paged", [("bf16", 128, 8, 2, True), ("bf16", 64, 4, 4, False),
+                                                  ("f32", 64, 4, 2, True), ("f32", 256, 2, 1, True)])
+def test_compaction_moves_the_kept_tokens_to_the_front(kb, dtype, d, Hq, Hkv, paged):
+    L, B, cap, T = 3, 3, 208, 200
+    share = np.array([0, 1, 1], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, dtype, cap, share, paged=paged, seed=31, fill_tokens=T)
+    rng = np.random.default_rng(31)
+    keep = _keep_lists(rng, B, Hkv, [T] * B, 0.05, 0.95)
+    keep[0][0] = np.arange(T, dtype=np.int32)                 # keep everything: nothing may change
+    keep[1][0] = np.array([T - 1], np.int32)                  # keep only the last token
+    idx, cnt = _pack(keep, B, Hkv)
+    before = case.store.pool.clone()
+    assert kb.kvs_compact_kv(case.store, 2, idx, cnt) == kb.KVS_NOOP      # a recipient owns no cache
+    torch.cuda.synchronize()
+    assert torch.equal(before, case.store.pool)
+    assert kb.kvs_compact_kv(case.store, 1, idx, cnt) == kb.KVS_OK
+    Kc, Vc, counts = compact(case.K[1], case.V[1], keep)
+    for layer in (1, 2):                                      # the recipient sees the compacted donor
+        k, v = kb.kvs_gather_kv(case.store, layer, 0, T, B)
+        k, v = inputs.to_oracle_array(k), inputs.to_oracle_array(v)
+        for b in range(B):
+            for h in range(Hkv):
+                n = counts[b, h]
+                assert np.array_equal(k[b, :n, h], Kc[b, :n, h]), (layer, b, h)
+                assert np.array_equal(v[b, :n, h], Vc[b, :n, h]), (layer, b, h)
+    k0, v0 = kb.kvs_gather_kv(case.store, 0, 0, T, B)         # the other slot is untouched
+    assert np.array_equal(inputs.to_oracle_array(k0), case.K[0])
+    assert np.array_equal(inputs.to_oracle_array(v0), case.V[0])
+
+
+@pytest.mark.parametrize("dtype,d,Hq,Hkv,split", [("bf16", 128, 8, 2, 0), ("bf16", 128, 8, 2, 64), ("bf16", 64, 8, 8, 0),
+                                                  ("f32", 64, 4, 2, 0)])
+def test_attention_over_kept_sets_matches_the_oracle(kb, dtype, d, Hq, Hkv, split):
+    L, B, cap = 4, 3, 528
+    share = np.array([0, 1, 0, 1], np.int32)                 # slots: layer 0 -> 0, layer 1 -> 1
+    n_tok = [512, 301, 77]
+    case = Case(kb, L, Hq, Hkv, d, B, dtype, cap, share, paged=True, seed=32, fill_tokens=512)
+    rng = np.random.default_rng(32)
+    keeps = {0: _keep_lists(rng, B, Hkv, n_tok, 0.3, 0.9), 1: _keep_lists(rng, B, Hkv, n_tok, 0.1, 1.0)}
+    keeps[1][2][0] = np.array([], np.int32)                   # a head that kept nothing: zero rows
+    kv_lens = np.zeros((2, B, Hkv), np.int32)
+    for donor in (0, 1):
+        idx, cnt = _pack(keeps[donor], B, Hkv)
+        assert kb.kvs_compact_kv(case.store, donor, idx, cnt) == kb.KVS_OK
+        kv_lens[donor] = cnt
+    q = inputs.normal((B, Hq, d), 32, 900, dtype=dtype)
+    assert kb.lib().kvs_set_split_tokens(split) == kb.KVS_OK
+    try:
+        for layer in range(L):
+            got = kb.kvs_decode_attention_per_head(case.store, layer, q.cuda(), kv_lens).cpu().numpy()
+            donor = share[layer]
+            want = sparse_decode_attention(inputs.to_oracle_array(q), case.K[donor], case.V[donor], keeps[donor])
+            assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION, layer
+            if donor == 1:
+                group = Hq // Hkv
+                assert np.all(got[2, :group] == 0)            # the empty head's query heads
+    finally:
+        assert kb.lib().kvs_set_split_tokens(0) == kb.KVS_OK
+
+
+def test_eviction_step_overwrites_or_extends_per_head(kb):
+    """One decode step of a token-dropping policy: the new token of each kv head either replaces
+    the token that head evicts or extends the head's list; then attention over the new sets."""
+    L, Hq, Hkv, d, B, cap, T = 2, 8, 4, 128, 2, 96, 80
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, "bf16", cap, share, paged=True, seed=33, fill_tokens=T)
+    rng = np.random.default_rng(33)
+    keep = _keep_lists(rng, B, Hkv, [T] * B, 0.4, 0.8)
+    idx, cnt = _pack(keep, B, Hkv)
+    assert kb.kvs_compact_kv(case.store, 0, idx, cnt) == kb.KVS_OK
+    Kc, Vc, counts = compact(case.K[0], case.V[0], keep, capacity=cap)
+    k_new = inputs.normal((B, 1, Hkv, d), 33, 700)
+    v_new = inputs.normal((B, 1, Hkv, d), 33, 701)
+    pos = np.zeros((B, Hkv), np.int32)
+    lens = counts.copy()
+    for b in range(B):
+        for h in range(Hkv):
+            if (b + h) % 2 == 0:                              # evict a random kept token, reuse its place
+                pos[b, h] = rng.integers(0, counts[b, h])
+            else:                                             # nothing evicted: the list grows
+                pos[b, h] = counts[b, h]
+                lens[b, h] += 1
+            Kc[b, pos[b, h], h] = inputs.to_oracle_array(k_new)[b, 0, h]
+            Vc[b, pos[b, h], h] = inputs.to_oracle_array(v_new)[b, 0, h]
+    assert kb.kvs_append_kv_per_head(case.store, 1, k_new.cuda(), v_new.cuda(), pos) == kb.KVS_NOOP
+    assert kb.kvs_append_kv_per_head(case.store, 0, k_new.cuda(), v_new.cuda(), pos) == kb.KVS_OK
+    k, v = kb.kvs_gather_kv(case.store, 1, 0, cap, B)
+    k, v = inputs.to_oracle_array(k), inputs.to_oracle_array(v)
+    for b in range(B):
+        for h in range(Hkv):
+            n = lens[b, h]
+            assert np.array_equal(k[b, :n, h], Kc[b, :n, h]) and np.array_equal(v[b, :n, h], Vc[b, :n, h]), (b, h)
+    q = inputs.normal((B, Hq, d), 33, 702)
+    front = [[np.arange(lens[b, h]) for h in range(Hkv)] for b in range(B)]
+    want = sparse_decode_attention(inputs.to_oracle_array(q), Kc, Vc, front)
+    got = kb.kvs_decode_attention_per_head(case.store, 1, q.cuda(), lens[None]).cpu().numpy()
+    assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
+
+
+def test_several_rows_per_head_cross_pages(kb):
+    """Per-head positions with more than one new row (the page-wise append path) and ragged starts."""
+    L, Hq, Hkv, d, B, cap = 1, 4, 2, 128, 2, 96
+    case = Case(kb, L, Hq, Hkv, d, B, "bf16", cap, np.array([0], np.int32), paged=True, seed=34, fill_tokens=40)
+    k_new = inputs.normal((B, 21, Hkv, d), 34, 800)
+    v_new = inputs.normal((B, 21, Hkv, d), 34, 801)
+    pos = np.array([[3, 40], [14, 75]], np.int32)
+    assert kb.kvs_append_kv_per_head(case.store, 0, k_new.cuda(), v_new.cuda(), pos) == kb.KVS_OK
+    k, v = kb.kvs_gather_kv(case.store, 0, 0, cap, B)
+    k, v = inputs.to_oracle_array(k), inputs.to_oracle_array(v)
+    kn, vn = inputs.to_oracle_array(k_new), inputs.to_oracle_array(v_new)
+    for b in range(B):
+        for h in range(Hkv):
+            p = pos[b, h]
+            assert np.array_equal(k[b, p:p + 21, h], kn[b, :, h]) and np.array_equal(v[b, p:p + 21, h], vn[b, :, h])
+            untouched = [t for t in range(40) if not p <= t < p + 21]
+            assert np.array_equal(k[b, untouched, h], case.K[0][b, untouched, h])
+            assert np.array_equal(v[b, untouched, h], case.V[0][b, untouched, h])

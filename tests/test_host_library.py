@@ -178,6 +178,17 @@ def test_entry_points_reject_bad_arguments_without_touching_the_gpu():
     assert proj(0, nws=8) == kb.KVS_ERR_INVALID_ARG and "workspace" in kb.last_error()
     assert lib.kvs_project_append_kv(C.byref(_fake_store(dtype=kb.KVS_F32, head_dim=64)), 0, p, 256, p, p, None, None, 0,
                                      p, 1, 1, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
+    # sparsified slots: per-head append and compaction are no-ops for recipients, bad arguments are errors
+    assert lib.kvs_append_kv_per_head(C.byref(st), 3, p, p, p, 1, 1, None) == kb.KVS_NOOP
+    assert lib.kvs_append_kv_per_head(C.byref(st), 0, p, p, None, 1, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_compact_kv(C.byref(st), 3, p, p, 8, 1, None) == kb.KVS_NOOP
+    assert lib.kvs_compact_kv(C.byref(st), 0, None, p, 8, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_compact_kv(C.byref(st), 0, p, p, 0, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_compact_kv(C.byref(st), 0, p, p, 65, 1, None) == kb.KVS_ERR_CAPACITY
+    assert lib.kvs_compact_kv(C.byref(st), 7, p, p, 8, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_attention_per_head(C.byref(st), 0, p, None, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_attention_per_head(C.byref(st), 0, None, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_attention_per_head(C.byref(st), 5, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     # distance
     assert lib.kvs_layer_distance(None, 1, 2, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_layer_distance(p, 1, 65, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
