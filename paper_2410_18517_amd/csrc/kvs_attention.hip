@@ -341,9 +341,9 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a)
 // O^T[channel][column] += V^T(16 x 32 tokens) . P^T(32 tokens x 16 columns) without any data
 // leaving its registers.
 template <int D>
-struct PageRegs {
-    uint4 k[D / 32];
-    uint4 v[D / 32];
+struct PageRegs {          // native vectors: they stay in registers when passed by reference
+    u32x4 k[D / 32];
+    u32x4 v[D / 32];
 };
 
 template <int D>
@@ -353,9 +353,9 @@ __device__ __forceinline__ void load_page(PageRegs<D>& r, const unsigned short* 
     const u32x4* kp = reinterpret_cast<const u32x4*>(pool + page_off) + lane;
     const u32x4* vp = kp + (kPageTokens * D * 2) / 16;
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) r.k[s] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(kp + s * 64));
+    for (int s = 0; s < D / 32; ++s) r.k[s] = __builtin_nontemporal_load(kp + s * 64);
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) r.v[s] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(vp + s * 64));
+    for (int s = 0; s < D / 32; ++s) r.v[s] = __builtin_nontemporal_load(vp + s * 64);
 }
 
 // Zero the values of tokens `first`.. of this lane's four (first <= 0 clears all four): the
@@ -412,6 +412,93 @@ __device__ __forceinline__ float column_sum(float x)
     x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
     auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// One softmax / accumulation step over a pair of pages (32 tokens) for the NT column tiles of a
+// wavefront: pa and pb hold the pages' operands (pb absent: have_b false), tok_a / tok_b are
+// their first token positions, n_col[ct] the number of keys the lane's column of tile ct sees,
+// n_min / n_max the fewest / most keys any column of the wavefront sees.
+template <int D, int NT>
+__device__ __forceinline__ void consume_pair(PageRegs<D>& pa, PageRegs<D>& pb, bool have_b, int tok_a, int tok_b,
+                                             int n_min, int n_max, const int (&n_col)[NT],
+                                             const bf16x8 (&qf)[NT][D / 32], float (&m)[NT], float (&l)[NT],
+                                             floatx4 (&o)[NT][D / 16], int quad, float scale_log2)
+{
+    constexpr int KS = D / 32, DT = D / 16;
+    // tokens past the stored length hold whatever the allocation held: clear their
+    // values so a zero probability cannot meet a NaN
+    if (tok_a + kPageTokens > n_max) clear_values_from<D>(pa, n_max - tok_a - quad * 4);
+    if (!have_b) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) pb.k[s] = pb.v[s] = u32x4{0u, 0u, 0u, 0u};
+    } else if (tok_b + kPageTokens > n_max) {
+        clear_values_from<D>(pb, n_max - tok_b - quad * 4);
+    }
+    const bool need_mask = !have_b || tok_b + kPageTokens > n_min || tok_a + kPageTokens > n_min;
+
+    floatx4 sa[NT], sb[NT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) sa[ct] = sb[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            sa[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa.k[s]), qf[ct][s],
+                                                             sa[ct], 0, 0, 0);
+            sb[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pb.k[s]), qf[ct][s],
+                                                             sb[ct], 0, 0, 0);
+        }
+    bf16x8 pf[NT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        float z[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            z[i] = sa[ct][i] * scale_log2;
+            z[4 + i] = sb[ct][i] * scale_log2;
+        }
+        if (need_mask) {
+            const int ta = tok_a + quad * 4, tb = tok_b + quad * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                z[i] = (ta + i < n_col[ct]) ? z[i] : -INFINITY;
+                z[4 + i] = (have_b && tb + i < n_col[ct]) ? z[4 + i] : -INFINITY;
+            }
+        }
+        const float mx = column_max(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
+                                          fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
+        // m is the reference of the exponentials, not necessarily the running maximum:
+        // softmax is shift invariant, so the reference only moves (and o, l are only
+        // rescaled) when a score exceeds it by more than kRefSlack; until then weights
+        // may reach 2^kRefSlack, which fp32 sums and bf16 operands hold without loss.
+        const bool up = mx > m[ct] + kRefSlack;              // false while everything is masked
+        const float m_new = up ? mx : m[ct];
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;   // column sees nothing yet
+        float p[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_use);
+        if (__any(up)) {
+            const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_use);   // 1 in lanes that keep their reference
+            l[ct] *= alpha;
+#pragma unroll
+            for (int c = 0; c < DT; ++c) o[ct][c] *= alpha;
+            m[ct] = m_new;
+        }
+        l[ct] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        const uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
+                                    pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+        pf[ct] = __builtin_bit_cast(bf16x8, pw);
+    }
+#pragma unroll
+    for (int c = 0; c < DT; ++c) {
+        const u32x4 va = pa.v[c >> 1], vb = pb.v[c >> 1];
+        // contraction slots 0-3: tokens 4*quad.. of the first page, 4-7: of the second
+        const u32x4 vcat = (c & 1) ? u32x4{va.z, va.w, vb.z, vb.w} : u32x4{va.x, va.y, vb.x, vb.y};
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct)
+            o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vcat), pf[ct],
+                                                               o[ct][c], 0, 0, 0);
+    }
 }
 
 template <int D, int NT, int kPrefetch>
@@ -553,80 +640,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             const int page_a = my_first + ka * kWaves, page_b = my_first + kb * kWaves;
             const int tok_a = page_a * kPageTokens, tok_b = page_b * kPageTokens;
 
-            // tokens past the stored length hold whatever the allocation held: clear their
-            // values so a zero probability cannot meet a NaN
-            if (tok_a + kPageTokens > n_max) clear_values_from<D>(pa, n_max - tok_a - quad * 4);
-            if (!have_b) {
-#pragma unroll
-                for (int s = 0; s < KS; ++s) pb.k[s] = pb.v[s] = make_uint4(0, 0, 0, 0);
-            } else if (tok_b + kPageTokens > n_max) {
-                clear_values_from<D>(pb, n_max - tok_b - quad * 4);
-            }
-            const bool need_mask = !have_b || tok_b + kPageTokens > n_min || tok_a + kPageTokens > n_min;
-
-            floatx4 sa[NT], sb[NT];
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) sa[ct] = sb[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < KS; ++s)
-#pragma unroll
-                for (int ct = 0; ct < NT; ++ct) {
-                    sa[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa.k[s]), qf[ct][s],
-                                                                     sa[ct], 0, 0, 0);
-                    sb[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pb.k[s]), qf[ct][s],
-                                                                     sb[ct], 0, 0, 0);
-                }
-            bf16x8 pf[NT];
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) {
-                float z[8];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    z[i] = sa[ct][i] * scale_log2;
-                    z[4 + i] = sb[ct][i] * scale_log2;
-                }
-                if (need_mask) {
-                    const int ta = tok_a + quad * 4, tb = tok_b + quad * 4;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        z[i] = (ta + i < n_col[ct]) ? z[i] : -INFINITY;
-                        z[4 + i] = (have_b && tb + i < n_col[ct]) ? z[4 + i] : -INFINITY;
-                    }
-                }
-                const float mx = column_max(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
-                                                  fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
-                // m is the reference of the exponentials, not necessarily the running maximum:
-                // softmax is shift invariant, so the reference only moves (and o, l are only
-                // rescaled) when a score exceeds it by more than kRefSlack; until then weights
-                // may reach 2^kRefSlack, which fp32 sums and bf16 operands hold without loss.
-                const bool up = mx > m[ct] + kRefSlack;              // false while everything is masked
-                const float m_new = up ? mx : m[ct];
-                const float m_use = m_new == -INFINITY ? 0.f : m_new;   // column sees nothing yet
-                float p[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_use);
-                if (__any(up)) {
-                    const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_use);   // 1 in lanes that keep their reference
-                    l[ct] *= alpha;
-#pragma unroll
-                    for (int c = 0; c < DT; ++c) o[ct][c] *= alpha;
-                    m[ct] = m_new;
-                }
-                l[ct] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-                const uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
-                                            pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-                pf[ct] = __builtin_bit_cast(bf16x8, pw);
-            }
-#pragma unroll
-            for (int c = 0; c < DT; ++c) {
-                const uint4 va = pa.v[c >> 1], vb = pb.v[c >> 1];
-                // contraction slots 0-3: tokens 4*quad.. of the first page, 4-7: of the second
-                const uint4 vcat = (c & 1) ? make_uint4(va.z, va.w, vb.z, vb.w) : make_uint4(va.x, va.y, vb.x, vb.y);
-#pragma unroll
-                for (int ct = 0; ct < NT; ++ct)
-                    o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vcat), pf[ct],
-                                                                       o[ct][c], 0, 0, 0);
-            }
+            consume_pair<D, NT>(pa, pb, have_b, tok_a, tok_b, n_min, n_max, n_col, qf, m, l, o, quad, scale_log2);
             if (ka + kPrefetch < my_pages)
                 load_page<D>(pa, pool, page_offset(st, slot, safe_block_of(st, b, page_a + kPrefetch * kWaves), g), lane);
             if (kb + kPrefetch < my_pages)
@@ -731,6 +745,165 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     }
 }
 
+// ------------------------------------------------------------------ wide prefill
+// Prefill with many query columns per (sequence, kv head).  The kernel above gives a workgroup
+// 64 columns and lets its wavefronts share out the pages, so every 64 columns stream the whole
+// prefix again: 64 flops per byte, which the memory system, not the matrix cores, then bounds.
+// Here the wavefronts of a workgroup each take their own columns (256 per workgroup as 8 x 32, or
+// 64 as 4 x 16 when a head has fewer) and all consume the same page pair: the pair is fetched once per workgroup (each thread a few 16-byte pieces, one
+// pair ahead, in registers), laid into LDS as the plain image of the two pages -- the in-page
+// order is the operand order, so a lane's operand is the 16 bytes at its own index -- and read
+// back by each wavefront after a barrier.  A wavefront owns its columns for the whole context:
+// no state is merged, no splits, the output is written normalised.  Causality: a wavefront
+// skips the pairs that lie beyond the last key any of its columns sees.
+// NT 16-column tiles per wavefront, WAVES wavefronts: NT * 16 * WAVES columns per workgroup.
+template <int D, int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3 : 2)))
+void attn_bf16_wide_kernel(AttnArgs a)
+{
+    constexpr int KS = D / 32, DT = D / 16;
+    constexpr int kWideThreads = WAVES * 64, kWideCols = WAVES * NT * 16;
+    constexpr int kPageVecs = kPageTokens * D * 2 * 2 / 16;        // 16-byte pieces of one page (K then V)
+    const StoreView& st = a.st;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int quad = lane >> 4, col = lane & 15;
+    const int g = blockIdx.x, b = blockIdx.y, cblk = blockIdx.z;
+    const int group = st.Hq / st.Hkv;
+    const int ncols = a.T_new * group;
+    const int cap = st.max_blocks_per_seq * kPageTokens;
+    const int slot = resolve_slot(st);
+
+    int n0 = a.lens[b] + a.lens_bias;                              // keys visible to query row 0
+    n0 = n0 < 0 ? 0 : n0;
+    if (n0 > cap - (a.T_new - 1)) n0 = cap - (a.T_new - 1);
+
+    // this lane's columns and their query fragments
+    const int c_lo = cblk * kWideCols + wave * (NT * 16);
+    size_t q_off[NT];
+    bool col_ok[NT];
+    int n_col[NT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        const int cidx = c_lo + ct * 16 + col;
+        col_ok[ct] = cidx < ncols;
+        const int row = col_ok[ct] ? cidx / group : 0;
+        const int hc = col_ok[ct] ? cidx % group : 0;
+        q_off[ct] = (((size_t)b * a.T_new + row) * st.Hq + g * group + hc) * D;
+        n_col[ct] = n0 + row;
+    }
+    bf16x8 qf[NT][KS];
+    const unsigned short* qbase = static_cast<const unsigned short*>(a.q);
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            uint4 w = make_uint4(0, 0, 0, 0);
+            if (col_ok[ct]) w = *reinterpret_cast<const uint4*>(qbase + q_off[ct] + s * 32 + quad * 8);
+            qf[ct][s] = __builtin_bit_cast(bf16x8, w);
+        }
+    const bool wave_has = c_lo < ncols;
+    int c_hi = c_lo + NT * 16 - 1;
+    if (c_hi > ncols - 1) c_hi = ncols - 1;
+    const int n_min = wave_has ? n0 + c_lo / group : 0;            // fewest keys any of the wavefront's rows sees
+    const int n_max = wave_has ? n0 + c_hi / group : 0;            // most
+    const int my_pages = (n_max + kPageTokens - 1) / kPageTokens;
+    int wg_hi = cblk * kWideCols + kWideCols - 1;
+    if (wg_hi > ncols - 1) wg_hi = ncols - 1;
+    const int wg_pages = (n0 + wg_hi / group + kPageTokens - 1) / kPageTokens;
+    const int wg_pairs = (wg_pages + 1) / 2;
+
+    __shared__ u32x4 tile[2][2 * kPageVecs];
+    const unsigned short* pool = static_cast<const unsigned short*>(st.pool);
+    // kDepth page pairs are in flight from global memory to registers at any time (a workgroup
+    // walks its pairs one after another, so the bytes it keeps in flight are all that hides the
+    // memory latency); slot k of `stage` holds the pairs with index = k mod kDepth.
+    constexpr int kDepth = NT == 1 ? 2 : 4;                        // fewer registers where occupancy matters more
+    constexpr int kPasses = (kPageVecs + kWideThreads - 1) / kWideThreads;   // passes of the workgroup over one page
+    u32x4 stage[kDepth][2 * kPasses];
+    // Each page of the pair is copied by whole passes of the workgroup, so that the page index --
+    // and with it the page-table entry -- is the same for every thread of a pass: a scalar load,
+    // which does not queue behind the vector loads already in flight.
+#define KVS_FETCH_PAIR(pair, slot_)                                                                   \
+    _Pragma("unroll") for (int pg = 0; pg < 2; ++pg) {                                                \
+        int page = 2 * (pair) + pg;                                                                   \
+        page = page < wg_pages ? page : wg_pages - 1;        /* an absent second page: nobody reads it */ \
+        const u32x4* src = reinterpret_cast<const u32x4*>(pool + page_offset(st, slot, safe_block_of(st, b, page), g)); \
+        _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                         \
+            const int v = i * kWideThreads + (int)threadIdx.x;                                        \
+            if (kPageVecs % kWideThreads == 0 || v < kPageVecs) stage[slot_][pg * kPasses + i] = src[v]; \
+        }                                                                                             \
+    }
+#define KVS_PUT_PAIR(buf, slot_)                                                                      \
+    _Pragma("unroll") for (int pg = 0; pg < 2; ++pg)                                                  \
+        _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                         \
+            const int v = i * kWideThreads + (int)threadIdx.x;                                        \
+            if (kPageVecs % kWideThreads == 0 || v < kPageVecs)                                       \
+                tile[buf][pg * kPageVecs + v] = stage[slot_][pg * kPasses + i];                       \
+        }
+
+    const float scale_log2 = 1.44269504088896340736f * (D == 128 ? 0.08838834764831845f : 0.125f);
+    float m[NT], l[NT];
+    floatx4 o[NT][DT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        m[ct] = -INFINITY;
+        l[ct] = 0.f;
+#pragma unroll
+        for (int c = 0; c < DT; ++c) o[ct][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+#pragma unroll
+    for (int j = 0; j < kDepth; ++j)
+        if (j < wg_pairs) { KVS_FETCH_PAIR(j, j) }
+    if (wg_pairs > 0) {
+        KVS_PUT_PAIR(0, 0)
+        if (kDepth < wg_pairs) { KVS_FETCH_PAIR(kDepth, 0) }
+    }
+    __syncthreads();
+    for (int p0 = 0; p0 < wg_pairs; p0 += kDepth) {
+#pragma unroll
+        for (int j = 0; j < kDepth; ++j) {
+            const int pair = p0 + j;
+            if (pair < wg_pairs) {                                     // uniform over the workgroup
+                const int buf = j & 1;                                 // kDepth is even
+                const int tok_a = 2 * pair * kPageTokens, tok_b = tok_a + kPageTokens;
+                if (tok_a < n_max) {
+                    const bool have_b = 2 * pair + 1 < my_pages;
+                    PageRegs<D> pa, pb;
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) {
+                        pa.k[s] = tile[buf][s * 64 + lane];
+                        pa.v[s] = tile[buf][(KS + s) * 64 + lane];
+                        pb.k[s] = have_b ? tile[buf][kPageVecs + s * 64 + lane] : u32x4{0u, 0u, 0u, 0u};
+                        pb.v[s] = have_b ? tile[buf][kPageVecs + (KS + s) * 64 + lane] : u32x4{0u, 0u, 0u, 0u};
+                    }
+                    consume_pair<D, NT>(pa, pb, have_b, tok_a, tok_b, n_min, n_max, n_col, qf, m, l, o, quad, scale_log2);
+                }
+                if (pair + 1 < wg_pairs) {
+                    KVS_PUT_PAIR(buf ^ 1, (j + 1) % kDepth)            // that buffer was last read before the previous barrier
+                    if (pair + 1 + kDepth < wg_pairs) { KVS_FETCH_PAIR(pair + 1 + kDepth, (j + 1) % kDepth) }
+                }
+                __syncthreads();
+            }
+        }
+    }
+#undef KVS_FETCH_PAIR
+#undef KVS_PUT_PAIR
+
+    // lane holds channels c*16 + 4*quad .. +3 of its column in o[ct][c]
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        const float lsum = column_sum(l[ct]);
+        if (!col_ok[ct]) continue;
+        const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+        const int cidx = c_lo + ct * 16 + col;
+        float* dst = a.out + (((size_t)b * a.T_new + cidx / group) * st.Hq + g * group + cidx % group) * D + quad * 4;
+#pragma unroll
+        for (int c = 0; c < DT; ++c) *reinterpret_cast<floatx4*>(dst + c * 16) = o[ct][c] * inv;
+    }
+}
+
 template <int D>
 int launch_bf16(const AttnArgs& a, hipStream_t s)
 {
@@ -738,6 +911,16 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
     if (a.T_new == 1) {
         dim3 grid(a.st.Hkv, a.B, a.n_splits);
         hipLaunchKernelGGL((attn_bf16_kernel<D, 1, 4>), grid, dim3(kThreads), 0, s, a);
+    } else if (const int ncols = a.T_new * group; ncols >= 256 && (long)a.st.Hkv * a.B * ((ncols + 255) / 256) >= 256) {
+        // Enough columns per (sequence, kv head) to share every page among eight wavefronts, and
+        // enough such workgroups to cover the chip without splitting the context.
+        dim3 grid(a.st.Hkv, a.B, (ncols + 255) / 256);
+        hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8>), grid, dim3(512), 0, s, a);
+    } else if (ncols >= 64 && (long)a.st.Hkv * a.B * ((ncols + 63) / 64) >= 512) {
+        // Fewer columns: 16 per wavefront, four wavefronts; small enough in registers for several
+        // workgroups per compute unit to hide each other's softmax arithmetic.
+        dim3 grid(a.st.Hkv, a.B, (ncols + 63) / 64);
+        hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4>), grid, dim3(256), 0, s, a);
     } else {
         const int cgroups = (a.T_new * group + 63) / 64;
         dim3 grid(a.st.Hkv, a.B, a.n_splits * cgroups);

@@ -191,6 +191,36 @@ def test_causal_prefill(kb, dtype, Hq, Hkv, d, T_new):
     assert rel_l2_rows(dec.cpu().numpy(), pre[:, -1].cpu().numpy().astype(np.float64)).max() <= REL_L2_ATTENTION
 
 
+# Shapes that reach each instantiation of the shared-page prefill kernel (a workgroup's wavefronts
+# take separate columns and read every page pair from LDS): it is used when one (sequence, kv
+# head) has at least 256 query columns (rows x group size) and there are at least 256 such
+# workgroups, or at least 64 columns and 512 workgroups.  Ragged column counts, a group size of two,
+# different start positions per sequence, a permuted page table, a recipient layer.
+@pytest.mark.parametrize("d,Hq,Hkv,B,T_new", [(128, 16, 8, 16, 150),     # 300 columns -> 2 x 256-column workgroups, 8 wavefronts
+                                              (128, 16, 8, 16, 100),     # 200 columns -> 4 x 64-column workgroups, 4 wavefronts
+                                              (64, 8, 8, 16, 300),       # head size 64, one query head per kv head
+                                              (64, 16, 8, 16, 100)])
+def test_shared_page_prefill_kernels(kb, d, Hq, Hkv, B, T_new):
+    L, cap = 2, 416
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, "bf16", cap, share, paged=True, seed=47)
+    rng = np.random.default_rng(47)
+    start = rng.integers(0, cap - T_new + 1, size=B).astype(np.int32)
+    start[0], start[-1] = 0, cap - T_new
+    q = case.q(1, rows=T_new)
+    got = kb.kvs_prefill_attention(case.store, 1, q.cuda(), start).cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in (0, B // 2, B - 1):
+        want = orc.shared_attention(1, share, [case.K[0][b:b + 1], None], [case.V[0][b:b + 1], None],
+                                    inputs.to_oracle_array(q[b:b + 1]), start[b:b + 1])
+        assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, b
+    # a row's output must not depend on which kernel computed it: the same rows as a short chunk
+    # (which takes the page-splitting kernel) agree to rounding
+    tail = 8
+    short = kb.kvs_prefill_attention(case.store, 1, q[:, -tail:].contiguous().cuda(), start + (T_new - tail)).cpu().numpy()
+    assert rel_l2_rows(short, got[:, -tail:].astype(np.float64)).max() <= REL_L2_ATTENTION
+
+
 def test_randomised_shapes_maps_and_lengths(kb):
     """Seeded sweep over store types, head groupings, batch sizes, sharing maps, paging, split sizes
     and ragged lengths; every case is compared element by element with the oracle."""

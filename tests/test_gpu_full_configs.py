@@ -100,3 +100,25 @@ def test_distance_full_size(kb):
     got = kb.kvs_build_share_map(D.astype(np.float32), 14)
     want = osm.build_share_map(D.astype(np.float32), L, 14)
     assert (got[0], got[1].tolist(), got[2].tolist(), got[3], got[4]) == want and got[3] == 34
+
+
+def test_whole_prompt_prefill_full_size_sampled(kb):
+    """Llama-2-13B shape, the whole 2048-token prompt prefilled in one call (32 column groups of 64
+    rows per head): rows sampled from the first, a middle and the last group of two sequences."""
+    w = inputs.WORKLOADS["llama2-13b"]
+    T_new = w.context
+    share = inputs.make_share_map(w.L, w.n_shared, 1)
+    recipient = next(l for l in range(w.L) if share[l] != l)
+    donor = int(share[recipient])
+    case = Case(kb, w.L, w.Hq, w.Hkv, w.d, w.B, w.dtype, w.context, share, paged=True, seed=201,
+                fill_layers=[donor], fill_tokens=T_new, spare_blocks=0)
+    start = np.zeros(w.B, np.int32)
+    for layer in (donor, recipient):
+        q = case.q(layer, rows=T_new)
+        got = kb.kvs_prefill_attention(case.store, layer, q.cuda(), start).cpu().numpy()
+        assert np.isfinite(got).all()
+        for b in (0, w.B - 1):
+            for r0 in (0, 1000, T_new - 16):
+                want = orc.shared_attention(layer, share, _sub(case, case.K, b), _sub(case, case.V, b),
+                                            inputs.to_oracle_array(q[b:b + 1, r0:r0 + 16]), np.array([r0], np.int32))
+                assert rel_l2_rows(got[b:b + 1, r0:r0 + 16], want).max() <= REL_L2_ATTENTION, (layer, b, r0)
