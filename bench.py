@@ -37,7 +37,6 @@ def recorded_traffic(workload):
     workload or the kernel source has changed since the counters were taken."""
     import hashlib
     path = os.path.join(ROOT, "profiles", f"attn_bf16_decode_{workload}.traffic.txt")
-    src = os.path.join(ROOT, "paper_2410_18517_amd", "csrc", "kvs_attention.hip")
     if not os.path.exists(path):
         return None
     rec = {}
@@ -45,7 +44,10 @@ def recorded_traffic(workload):
         if "=" in line and not line.startswith("#"):
             k, v = line.split("=", 1)
             rec[k.strip()] = v.strip()
-    if rec.get("kernel_source_sha256") != hashlib.sha256(open(src, "rb").read()).hexdigest():
+    digest = hashlib.sha256()
+    for name in ("kvs_attention.hip", "kvs_device.h"):           # the decode kernel and the helpers it inlines
+        digest.update(open(os.path.join(ROOT, "paper_2410_18517_amd", "csrc", name), "rb").read())
+    if rec.get("kernel_source_sha256") != digest.hexdigest():
         return None
     return int(rec["traffic_bytes_per_launch"])
 

@@ -1,17 +1,17 @@
-// Attention over the slot-indexed, paged KV store (gfx950): append / gather, the fp32
-// reference-precision kernel, the bf16 split-context MFMA kernel and the split combine.
+// Attention over the slot-indexed, paged KV store (gfx950): the fp32 reference-precision kernel,
+// the bf16 split-context MFMA kernel with its split combine, and the shared-page prefill kernels.
 //
 // The operation is the ordinary attention of the host model after the sharing strategy has
 // redirected a layer to its donor's cache (paper Sec. 3.2): the only method-specific step in
 // the kernels is the two-level lookup slot_of_layer[share_map[layer]], done on the device.
 #include <hip/hip_runtime.h>
 
+#include "kvs_device.h"
 #include "kvs_internal.h"
 
 namespace kvs {
 namespace {
 
-constexpr int kPageTokens = 16;
 constexpr int kWaves = 4;              // wavefronts per workgroup of the bf16 kernel
 constexpr int kThreads = kWaves * 64;
 constexpr float kRefSlack = 8.f;       // log2 units a score may exceed the softmax reference by
@@ -22,232 +22,6 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ int resolve_slot(const StoreView& st)
-{
-    // the strategy's substitution: a layer reads the cache of its donor (itself if none)
-    int donor = st.share_map[st.layer];
-    donor = donor < 0 ? 0 : (donor >= st.L ? st.L - 1 : donor);
-    const int slot = st.slot_of_layer[donor];
-    return slot < 0 ? 0 : (slot >= st.n_slots ? st.n_slots - 1 : slot);
-}
-
-// Physical block of logical page `page` of sequence b.
-__device__ __forceinline__ int block_of(const StoreView& st, int b, int page)
-{
-    const size_t idx = (size_t)b * st.max_blocks_per_seq + page;
-    return st.block_table ? st.block_table[idx] : (int)idx;   // contiguous: the host checked B * max_blocks <= num_blocks
-}
-
-// Same, forced into the pool: a corrupt table entry must not turn into a wild read.
-__device__ __forceinline__ int safe_block_of(const StoreView& st, int b, int page)
-{
-    const int blk = block_of(st, b, page);
-    return blk < 0 ? 0 : (blk >= st.num_blocks ? st.num_blocks - 1 : blk);
-}
-
-// Element offset of the K page of (slot, block, kv head); the V page follows it.
-__device__ __forceinline__ size_t page_offset(const StoreView& st, int slot, int blk, int g)
-{
-    return (((size_t)slot * st.num_blocks + blk) * st.Hkv + g) * 2 * (size_t)(kPageTokens * st.head_dim);
-}
-
-// In-page element index of (token t, channel c) for the bf16 store.
-__device__ __forceinline__ int k_index_bf16(int t, int c)
-{
-    return (((c >> 5) * 4 + ((c & 31) >> 3)) * 16 + t) * 8 + (c & 7);
-}
-__device__ __forceinline__ int v_index_bf16(int t, int c)
-{
-    return ((((c >> 5) * 4 + (t >> 2)) * 16 + (c & 15)) * 2 + ((c >> 4) & 1)) * 4 + (t & 3);
-}
-
-// ------------------------------------------------------------------ append / gather
-// One thread moves 8 consecutive channels (bf16) or 4 (fp32) of one (sequence, row, kv head).
-template <bool kToStore>
-__global__ void copy_rows_kernel(CopyArgs a)
-{
-    const StoreView& st = a.st;
-    const int D = st.head_dim;
-    const int per = st.dtype == 1 ? 8 : 4;
-    const int chunks = D / per;
-    const long total = (long)a.B * a.T * st.Hkv * chunks;
-    const long tid = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid >= total) return;
-    const int ch = (int)(tid % chunks);
-    const int g = (int)((tid / chunks) % st.Hkv);
-    const int i = (int)((tid / ((long)chunks * st.Hkv)) % a.T);
-    const int b = (int)(tid / ((long)chunks * st.Hkv * a.T));
-    const long pos = (long)(a.start_pos ? a.start_pos[a.pos_per_head ? b * st.Hkv + g : b] : a.t0) + i;
-    if (pos < 0 || pos >= (long)st.max_blocks_per_seq * kPageTokens) return;
-    const int slot = resolve_slot(st);
-    const int blk = block_of(st, b, (int)(pos / kPageTokens));
-    if (blk < 0 || blk >= st.num_blocks) return;
-    const int t = (int)(pos % kPageTokens);
-    const size_t page = page_offset(st, slot, blk, g);
-    const size_t row = (((size_t)b * a.T + i) * st.Hkv + g) * D + (size_t)ch * per;
-    if (st.dtype == 1) {
-        unsigned short* pool = static_cast<unsigned short*>(st.pool);
-        unsigned short* kp = pool + page;
-        unsigned short* vp = kp + kPageTokens * D;
-        unsigned short* kr = static_cast<unsigned short*>(a.k) + row;
-        unsigned short* vr = static_cast<unsigned short*>(a.v) + row;
-        const int c0 = ch * 8;
-        if (kToStore) {
-            *reinterpret_cast<uint4*>(kp + k_index_bf16(t, c0)) = *reinterpret_cast<const uint4*>(kr);
-            const uint4 vv = *reinterpret_cast<const uint4*>(vr);
-            const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                vp[v_index_bf16(t, c0 + e)] = (unsigned short)(w[e >> 1] >> ((e & 1) * 16));
-        } else {
-            *reinterpret_cast<uint4*>(kr) = *reinterpret_cast<const uint4*>(kp + k_index_bf16(t, c0));
-            unsigned w[4] = {0, 0, 0, 0};
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                w[e >> 1] |= (unsigned)vp[v_index_bf16(t, c0 + e)] << ((e & 1) * 16);
-            *reinterpret_cast<uint4*>(vr) = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-    } else {
-        float* pool = static_cast<float*>(st.pool);
-        float* kp = pool + page + (size_t)t * D + ch * 4;
-        float* vp = kp + kPageTokens * D;
-        float* kr = static_cast<float*>(a.k) + row;
-        float* vr = static_cast<float*>(a.v) + row;
-        if (kToStore) {
-            *reinterpret_cast<float4*>(kp) = *reinterpret_cast<const float4*>(kr);
-            *reinterpret_cast<float4*>(vp) = *reinterpret_cast<const float4*>(vr);
-        } else {
-            *reinterpret_cast<float4*>(kr) = *reinterpret_cast<const float4*>(kp);
-            *reinterpret_cast<float4*>(vr) = *reinterpret_cast<const float4*>(vp);
-        }
-    }
-}
-
-// Append of several rows per sequence to a bf16 store (prefill chunks, store fills): one
-// workgroup per (sequence, kv head, page touched).  K rows go straight to their operand-order
-// position, 16 bytes per thread.  V rows are staged in LDS and leave as whole 16-byte operand
-// chunks (four tokens x two channels) wherever all four tokens of the chunk are being written;
-// the ragged first and last tokens of the append fall back to 2-byte stores.  A whole-page
-// append therefore writes each page as 4 KiB of full-width stores instead of 2-byte scatters.
-__global__ __launch_bounds__(256) void append_pages_bf16_kernel(CopyArgs a)
-{
-    const StoreView& st = a.st;
-    const int D = st.head_dim;                    // 64 or 128
-    const int g = blockIdx.y, b = blockIdx.z;
-    const long start = a.start_pos[a.pos_per_head ? b * st.Hkv + g : b];
-    const long cap = (long)st.max_blocks_per_seq * kPageTokens;
-    if (start < 0 || start >= cap) return;
-    const long end = start + a.T < cap ? start + a.T : cap;
-    const long page = start / kPageTokens + blockIdx.x;
-    const long tok0 = page * kPageTokens;
-    if (tok0 >= end) return;
-    const int t_lo = (int)(start > tok0 ? start - tok0 : 0);
-    const int t_hi = (int)(end - tok0 < kPageTokens ? end - tok0 : kPageTokens);
-    const int blk = block_of(st, b, (int)page);
-    if (blk < 0 || blk >= st.num_blocks) return;
-    unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, resolve_slot(st), blk, g);
-    unsigned short* vp = kp + kPageTokens * D;
-    __shared__ unsigned short vs[kPageTokens][128 + 8];
-
-    const int chunks = D / 8;                     // 16-byte chunks per row
-    const int t = threadIdx.x / 16, ch = threadIdx.x % 16;
-    if (t >= t_lo && t < t_hi && ch < chunks) {
-        const size_t row = (((size_t)b * a.T + (size_t)(tok0 + t - start)) * st.Hkv + g) * D + (size_t)ch * 8;
-        *reinterpret_cast<uint4*>(kp + k_index_bf16(t, ch * 8)) =
-            *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(a.k) + row);
-        *reinterpret_cast<uint4*>(&vs[t][ch * 8]) =
-            *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(a.v) + row);
-    }
-    __syncthreads();
-    // output chunk o: channels (o/64)*32 + {0,16} + o%16, tokens 4*((o/16)%4) .. +3
-    for (int o = threadIdx.x; o < D * 2; o += 256) {
-        const int cp = o / 64, quad = (o / 16) % 4, dl = o % 16;
-        unsigned short e[8];
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) e[j * 4 + i] = vs[quad * 4 + i][cp * 32 + j * 16 + dl];
-        unsigned short* dst = vp + (size_t)o * 8;
-        if (quad * 4 >= t_lo && quad * 4 + 4 <= t_hi) {
-            *reinterpret_cast<uint4*>(dst) = make_uint4(e[0] | (unsigned)e[1] << 16, e[2] | (unsigned)e[3] << 16,
-                                                        e[4] | (unsigned)e[5] << 16, e[6] | (unsigned)e[7] << 16);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (quad * 4 + i >= t_lo && quad * 4 + i < t_hi) dst[j * 4 + i] = e[j * 4 + i];
-        }
-    }
-}
-
-// In-place compaction of a slot after token eviction: for every (sequence, kv head) the tokens
-// at the increasing positions keep_idx[0 .. count) move to positions 0 .. count.  A workgroup
-// owns one (kv head, sequence) and two of the 16-byte channel pieces of its rows (pieces never
-// interact, so they spread over workgroups) and walks the destination in chunks of 128 tokens:
-// thread (t, piece) loads its piece of K and of V of source token keep_idx[chunk + t], the
-// workgroup meets at a barrier, then the pieces are stored at chunk + t.  Because
-// keep_idx[j] >= j, a chunk reads only positions at or behind its own start and writes only its
-// own 128 positions, so chunks never touch each other's data and one barrier per chunk is enough.
-constexpr int kCompactTokens = 128;
-template <bool kBf16>
-__global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
-{
-    const StoreView& st = a.st;
-    const int D = st.head_dim;
-    constexpr int per = kBf16 ? 8 : 4;
-    const int g = blockIdx.x, b = blockIdx.y;
-    const int ch = blockIdx.z * 2 + (threadIdx.x & 1);         // this thread's piece of the row
-    const int tt = threadIdx.x >> 1;
-    const int cap = st.max_blocks_per_seq * kPageTokens;
-    int count = a.keep_count[b * st.Hkv + g];
-    const int most = a.max_keep < cap ? a.max_keep : cap;
-    count = count < 0 ? 0 : (count > most ? most : count);
-    const int32_t* idx = a.keep_idx + ((size_t)b * st.Hkv + g) * a.max_keep;
-    const int slot = resolve_slot(st);
-    for (int c0 = 0; c0 < count; c0 += kCompactTokens) {
-        const int j = c0 + tt;
-        const bool active = j < count && ch * per < D;
-        int src = active ? idx[j] : 0;
-        src = src < 0 ? 0 : (src >= cap ? cap - 1 : src);
-        const int sblk = block_of(st, b, src / kPageTokens);
-        const int dblk = block_of(st, b, (j < cap ? j : cap - 1) / kPageTokens);
-        const bool ok = active && sblk >= 0 && sblk < st.num_blocks && dblk >= 0 && dblk < st.num_blocks;
-        const int ts = src % kPageTokens, td = j % kPageTokens;
-        uint4 kreg = make_uint4(0, 0, 0, 0), vreg = make_uint4(0, 0, 0, 0);
-        if (ok) {
-            if (kBf16) {
-                const unsigned short* kp = static_cast<const unsigned short*>(st.pool) + page_offset(st, slot, sblk, g);
-                const unsigned short* vp = kp + kPageTokens * D;
-                kreg = *reinterpret_cast<const uint4*>(kp + k_index_bf16(ts, ch * 8));
-                unsigned w[4] = {0, 0, 0, 0};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) w[e >> 1] |= (unsigned)vp[v_index_bf16(ts, ch * 8 + e)] << ((e & 1) * 16);
-                vreg = make_uint4(w[0], w[1], w[2], w[3]);
-            } else {
-                const float* kp = static_cast<const float*>(st.pool) + page_offset(st, slot, sblk, g) + (size_t)ts * D + ch * 4;
-                kreg = *reinterpret_cast<const uint4*>(kp);
-                vreg = *reinterpret_cast<const uint4*>(kp + kPageTokens * D);
-            }
-        }
-        __syncthreads();
-        if (ok) {
-            if (kBf16) {
-                unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, slot, dblk, g);
-                unsigned short* vp = kp + kPageTokens * D;
-                *reinterpret_cast<uint4*>(kp + k_index_bf16(td, ch * 8)) = kreg;
-                const unsigned w[4] = {vreg.x, vreg.y, vreg.z, vreg.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) vp[v_index_bf16(td, ch * 8 + e)] = (unsigned short)(w[e >> 1] >> ((e & 1) * 16));
-            } else {
-                float* kp = static_cast<float*>(st.pool) + page_offset(st, slot, dblk, g) + (size_t)td * D + ch * 4;
-                *reinterpret_cast<uint4*>(kp) = kreg;
-                *reinterpret_cast<uint4*>(kp + kPageTokens * D) = vreg;
-            }
-        }
-    }
-}
 
 // ------------------------------------------------------------------ fp32 store
 // One wavefront per (sequence, query row, query head); the whole context in one pass.
@@ -451,11 +225,11 @@ __device__ __forceinline__ void consume_pair(PageRegs<D>& pa, PageRegs<D>& pb, b
     bf16x8 pf[NT];
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) {
-        float z[8];
+        float z[8];                                          // raw scores; the scale is applied inside the exponent
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            z[i] = sa[ct][i] * scale_log2;
-            z[4 + i] = sb[ct][i] * scale_log2;
+            z[i] = sa[ct][i];
+            z[4 + i] = sb[ct][i];
         }
         if (need_mask) {
             const int ta = tok_a + quad * 4, tb = tok_b + quad * 4;
@@ -465,8 +239,8 @@ __device__ __forceinline__ void consume_pair(PageRegs<D>& pa, PageRegs<D>& pb, b
                 z[4 + i] = (have_b && tb + i < n_col[ct]) ? z[4 + i] : -INFINITY;
             }
         }
-        const float mx = column_max(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
-                                          fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
+        const float mx = scale_log2 * column_max(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
+                                                       fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
         // m is the reference of the exponentials, not necessarily the running maximum:
         // softmax is shift invariant, so the reference only moves (and o, l are only
         // rescaled) when a score exceeds it by more than kRefSlack; until then weights
@@ -476,7 +250,7 @@ __device__ __forceinline__ void consume_pair(PageRegs<D>& pa, PageRegs<D>& pb, b
         const float m_use = m_new == -INFINITY ? 0.f : m_new;   // column sees nothing yet
         float p[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_use);
+        for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(z[i], scale_log2, -m_use));
         if (__any(up)) {
             const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_use);   // 1 in lanes that keep their reference
             l[ct] *= alpha;
@@ -931,42 +705,6 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
 }
 
 }  // namespace
-
-int launch_append(const CopyArgs& a, void* stream)
-{
-    if (a.st.dtype == 1 && a.T >= 4) {
-        // pages a sequence's rows can touch: T rows starting anywhere inside a page
-        const unsigned pages = (unsigned)((a.T + kPageTokens - 1) / kPageTokens + 1);
-        hipLaunchKernelGGL(append_pages_bf16_kernel, dim3(pages, a.st.Hkv, a.B), dim3(256), 0,
-                           static_cast<hipStream_t>(stream), a);
-        return (int)hipGetLastError();
-    }
-    const int per = a.st.dtype == 1 ? 8 : 4;
-    const long total = (long)a.B * a.T * a.st.Hkv * (a.st.head_dim / per);
-    const unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(copy_rows_kernel<true>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), a);
-    return (int)hipGetLastError();
-}
-
-int launch_compact(const CompactArgs& a, void* stream)
-{
-    const int pieces = a.st.head_dim / (a.st.dtype == 1 ? 8 : 4);
-    const dim3 grid(a.st.Hkv, a.B, (pieces + 1) / 2);
-    if (a.st.dtype == 1)
-        hipLaunchKernelGGL(compact_kernel<true>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
-    else
-        hipLaunchKernelGGL(compact_kernel<false>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
-    return (int)hipGetLastError();
-}
-
-int launch_gather(const CopyArgs& a, void* stream)
-{
-    const int per = a.st.dtype == 1 ? 8 : 4;
-    const long total = (long)a.B * a.T * a.st.Hkv * (a.st.head_dim / per);
-    const unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(copy_rows_kernel<false>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), a);
-    return (int)hipGetLastError();
-}
 
 int launch_attention(const AttnArgs& a, void* stream)
 {
