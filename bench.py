@@ -22,12 +22,14 @@ HBM_PEAK_GBPS = 8000.0              # MI355X HBM3E, published peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak, published
 
 
-def algorithmic_bytes_per_launch(w, seq_lens):
+def algorithmic_bytes_per_launch(w, seq_lens, store_dtype=None):
     """Bytes one decode-attention launch must move: every stored key and value of the layer's
     slot once, q in, fp32 out, and the page-table entries that address the context."""
-    e = 2 if w.dtype == "bf16" else 4
+    store_dtype = store_dtype or w.dtype
+    e = {"fp8": 1, "bf16": 2}.get(store_dtype, 4)             # bytes per stored element
+    eq = 4 if store_dtype == "f32" else 2                      # queries are bf16 for bf16 and fp8 slots
     kv = int(seq_lens.astype(np.int64).sum()) * w.Hkv * w.d * 2 * e
-    qo = w.B * w.Hq * w.d * (e + 4)
+    qo = w.B * w.Hq * w.d * (eq + 4)
     table = int(((seq_lens.astype(np.int64) + 15) // 16).sum()) * 4
     return kv + qo + table
 
@@ -293,6 +295,8 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--store", choices=["fp8"], default=None,
+                    help="decode mode: keep the slots in fp8 (E4M3) instead of the workload's type")
     ap.add_argument("--prefill-rows", type=int, default=0,
                     help="--mode prefill: rows per sequence in the chunk (default: the workload's 64)")
     ap.add_argument("--project-rows", type=int, default=1,
@@ -332,7 +336,10 @@ def main():
     max_blocks = w.max_blocks_per_seq
     num_blocks = w.B * max_blocks
     table = inputs.make_block_table(w.B, max_blocks, num_blocks, 1)
-    store = kb.KVStore(share, w.Hq, w.Hkv, w.d, w.dtype, num_blocks, max_blocks, block_table=table)
+    store_dtype = args.store or w.dtype
+    if store_dtype == "fp8" and w.dtype != "bf16":
+        sys.exit("--store fp8 needs a bf16 workload")
+    store = kb.KVStore(share, w.Hq, w.Hkv, w.d, store_dtype, num_blocks, max_blocks, block_table=table)
     tdt = store.torch_dtype
 
     # fill every slot through the library's own append path; keep one layer's source rows for the oracle
@@ -374,6 +381,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    print("store filled, timing", file=sys.stderr, flush=True)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -399,19 +407,20 @@ def main():
         launch_ms.append((e0, e1))
     torch.cuda.synchronize()
     launch_ms = float(np.mean([a.elapsed_time(b) for a, b in launch_ms])) / w.L
-    alg_bytes = algorithmic_bytes_per_launch(w, seq_lens)
+    alg_bytes = algorithmic_bytes_per_launch(w, seq_lens, store_dtype)
     achieved = alg_bytes / (launch_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "attn_bf16_kernel<128,1> (one kvs_decode_attention launch)",
+    roofline = {"bound": "hbm", "kernel": "attn_bf16_kernel<128,1%s> (one kvs_decode_attention launch)" % (
+                    ", fp8 pages" if store_dtype == "fp8" else ""),
                 "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": recorded_traffic(w.name), "launch_us": round(launch_ms * 1e3, 2),
+                "traffic": recorded_traffic(w.name) if store_dtype == w.dtype else None, "launch_us": round(launch_ms * 1e3, 2),
                 "algorithmic_bytes": alg_bytes}
 
     result = {
         "metric": "shared-KV decode attention tokens/s", "value": round(tokens_per_s, 2), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "layers": w.L, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
+        "config": {"workload": w.name if store_dtype == w.dtype else f"{w.name}, {store_dtype} slots", "layers": w.L, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "batch": w.B, "context": w.context if w.min_context is None else [w.min_context, w.context],
                    "page_tokens": 16, "shared_layers": w.n_shared, "kv_slots": int(store.desc.n_slots)},
         "hbm_gbps": round(alg_bytes * w.L / (ms_per_step * 1e-3) / 1e9, 1),
@@ -420,9 +429,19 @@ def main():
     }
 
     if not args.no_cpu_baseline:
+        print("GPU part done, running the CPU oracle", file=sys.stderr, flush=True)
         from oracle import attention as orc
         K = [inputs.to_oracle_array(kept[l][0]) if l in kept else None for l in range(w.L)]
         V = [inputs.to_oracle_array(kept[l][1]) if l in kept else None for l in range(w.L)]
+        if store_dtype == "fp8":                   # the oracle attends to the values as the slots hold them
+            from oracle.fp8 import round_e4m3
+            # the storage oracle applied to every bf16 bit pattern once, then looked up per element
+            with np.errstate(invalid="ignore"):
+                every = (np.arange(1 << 16, dtype=np.uint32) << 16).view(np.float32).astype(np.float64)
+            lut = (round_e4m3(every).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+            K = [None if a is None else lut[a] for a in K]
+            V = [None if a is None else lut[a] for a in V]
+            print("fp8: oracle-side copies rounded", file=sys.stderr, flush=True)
         got_all = out.cpu().numpy().astype(np.float64)
         cpu_s, err = 0.0, 0.0
         for l in range(w.L):                       # the whole decode step, layer by layer

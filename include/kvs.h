@@ -32,6 +32,14 @@
  *               reads 1 KiB contiguous per load and feeds it to MFMA untransposed:
  *       K page: element (token t, channel c) at (((c/32)*4 + (c%32)/8)*16 + t)*8 + c%8
  *       V page: element (t, c) at ((((c/32)*4 + t/4)*16 + c%16)*2 + (c/16)%2)*4 + t%4
+ *     KVS_FP8 : one byte per element, the OCP 8-bit float E4M3 (bias 7, largest value 448, no
+ *               infinities), unscaled; rows and queries cross the boundary as bf16.  An append
+ *               rounds to nearest, ties to even, saturating at +-448 (NaN stays NaN); a gather
+ *               returns the stored values exactly.  The attention kernels widen the bytes to
+ *               bf16 in registers and then run the bf16 path, so a slot costs half the HBM
+ *               bytes of a bf16 slot per decode step.  In-page order, again the operand order:
+ *       K page: element (t, c) at (((c/64)*4 + (c%32)/8)*16 + t)*16 + ((c/32)%2)*8 + c%8
+ *       V page: element (t, c) at (((c/64)*4 + t/4)*16 + c%16)*16 + ((c/16)%4)*4 + t%4
  *   Only kvs_append_kv writes pages and only the attention kernels / kvs_gather_kv read
  *   them, so callers never depend on the in-page order.
  */
@@ -56,6 +64,7 @@ extern "C" {
 
 #define KVS_F32   0
 #define KVS_BF16  1
+#define KVS_FP8   2   /* store only: q, k_new, v_new and gathered rows are bf16 */
 
 #define KVS_BLOCK_TOKENS 16
 
@@ -101,7 +110,7 @@ typedef struct kvs_desc {
     int32_t L;                   /* layers of the model */
     int32_t n_slots;             /* layer caches actually held: L - (shared layers) */
     int32_t Hq, Hkv, head_dim;   /* Hq % Hkv == 0; query head h reads kv head h / (Hq/Hkv) */
-    int32_t dtype;               /* KVS_F32 or KVS_BF16: element type of the store and of q, k_new, v_new */
+    int32_t dtype;               /* KVS_F32, KVS_BF16: element type of the store and of q, k_new, v_new; KVS_FP8: see above */
     int32_t block_tokens;        /* must be KVS_BLOCK_TOKENS */
     int32_t num_blocks;          /* blocks per slot */
     int32_t max_blocks_per_seq;  /* columns of the block table; capacity = 16 * this */

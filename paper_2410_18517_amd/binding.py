@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libkvs.so")
 KVS_OK, KVS_NOOP = 0, 1
 KVS_ERR_INVALID_ARG, KVS_ERR_BAD_MAP, KVS_ERR_CAPACITY = -1, -2, -3
 KVS_ERR_TARGET_UNREACHED, KVS_ERR_UNSUPPORTED, KVS_ERR_HIP = -4, -5, -6
-KVS_F32, KVS_BF16 = 0, 1
+KVS_F32, KVS_BF16, KVS_FP8 = 0, 1, 2
 KVS_BLOCK_TOKENS = 16
 
 EXPORTS = [
@@ -155,7 +155,7 @@ def kvs_set_split_tokens(tokens: int):
 
 # ------------------------------------------------------------------ store
 
-_TORCH_DTYPE = {KVS_F32: torch.float32, KVS_BF16: torch.bfloat16}
+_TORCH_DTYPE = {KVS_F32: torch.float32, KVS_BF16: torch.bfloat16, KVS_FP8: torch.bfloat16}   # of rows and queries
 
 
 class KVStore:
@@ -167,7 +167,8 @@ class KVStore:
         self.host_share_map = _i32(share_map)
         L = len(self.host_share_map)
         self.host_slot_of_layer, n_slots = kvs_slots_from_share_map(self.host_share_map)
-        self.dtype = KVS_BF16 if dtype in ("bf16", KVS_BF16, torch.bfloat16) else KVS_F32
+        self.dtype = (KVS_FP8 if dtype in ("fp8", KVS_FP8) else
+                      KVS_BF16 if dtype in ("bf16", KVS_BF16, torch.bfloat16) else KVS_F32)
         self.desc = kvs_desc(L, n_slots, Hq, Hkv, head_dim, self.dtype, KVS_BLOCK_TOKENS,
                              num_blocks, max_blocks_per_seq)
         nbytes = lib().kvs_store_bytes(C.byref(self.desc))

@@ -6,6 +6,8 @@
 // the kernels is the two-level lookup slot_of_layer[share_map[layer]], done on the device.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kvs_device.h"
 #include "kvs_internal.h"
 
@@ -121,15 +123,60 @@ struct PageRegs {          // native vectors: they stay in registers when passed
 };
 
 template <int D>
-__device__ __forceinline__ void load_page(PageRegs<D>& r, const unsigned short* pool, size_t page_off, int lane)
+__device__ __forceinline__ void load_page(PageRegs<D>& r, const void* pool, size_t page_off, int lane)
 {
     // Every key and value is read once per launch: stream them past the caches.
-    const u32x4* kp = reinterpret_cast<const u32x4*>(pool + page_off) + lane;
+    const u32x4* kp = reinterpret_cast<const u32x4*>(static_cast<const unsigned short*>(pool) + page_off) + lane;
     const u32x4* vp = kp + (kPageTokens * D * 2) / 16;
 #pragma unroll
     for (int s = 0; s < D / 32; ++s) r.k[s] = __builtin_nontemporal_load(kp + s * 64);
 #pragma unroll
     for (int s = 0; s < D / 32; ++s) r.v[s] = __builtin_nontemporal_load(vp + s * 64);
+}
+
+// The same page in the fp8 store: half the registers, and one 16-byte load carries two
+// contraction steps of K (or four channel tiles of V).
+template <int D>
+struct PageRegs8 {
+    u32x4 k[D / 64];
+    u32x4 v[D / 64];
+};
+
+template <int D>
+__device__ __forceinline__ void load_page(PageRegs8<D>& r, const void* pool, size_t page_off, int lane)
+{
+    const u32x4* kp = reinterpret_cast<const u32x4*>(static_cast<const unsigned char*>(pool) + page_off) + lane;
+    const u32x4* vp = kp + (kPageTokens * D) / 16;
+#pragma unroll
+    for (int s = 0; s < D / 64; ++s) r.k[s] = __builtin_nontemporal_load(kp + s * 64);
+#pragma unroll
+    for (int s = 0; s < D / 64; ++s) r.v[s] = __builtin_nontemporal_load(vp + s * 64);
+}
+
+// Four E4M3 bytes -> four bf16 (two words), exactly: every E4M3 value is a bf16 value.
+__device__ __forceinline__ void widen4(unsigned w, unsigned& lo, unsigned& hi)
+{
+    const floatx2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+    const floatx2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+    lo = __builtin_bit_cast(unsigned, __builtin_convertvector(a, bf16x2));
+    hi = __builtin_bit_cast(unsigned, __builtin_convertvector(b, bf16x2));
+}
+
+// fp8 page registers -> the bf16 operand registers the arithmetic below works on.
+template <int D>
+__device__ __forceinline__ void widen(const PageRegs8<D>& r, PageRegs<D>& o)
+{
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+        const u32x4 kk = r.k[s >> 1], vv = r.v[s >> 1];
+        unsigned a0, a1, b0, b1;
+        widen4((s & 1) ? kk.z : kk.x, a0, a1);        // channels 8*quad .. +3 of step s, then +4 .. +7
+        widen4((s & 1) ? kk.w : kk.y, b0, b1);
+        o.k[s] = u32x4{a0, a1, b0, b1};
+        widen4((s & 1) ? vv.z : vv.x, a0, a1);        // channel tile 2s: tokens 4*quad .. +3
+        widen4((s & 1) ? vv.w : vv.y, b0, b1);        // channel tile 2s + 1
+        o.v[s] = u32x4{a0, a1, b0, b1};
+    }
 }
 
 // Zero the values of tokens `first`.. of this lane's four (first <= 0 clears all four): the
@@ -275,7 +322,7 @@ __device__ __forceinline__ void consume_pair(PageRegs<D>& pa, PageRegs<D>& pb, b
     }
 }
 
-template <int D, int NT, int kPrefetch>
+template <int D, int NT, int kPrefetch, bool kFp8>
 __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 {
     // kPrefetch: pages each wavefront keeps in flight (consumed in pairs)
@@ -378,11 +425,12 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     const int live_splits = (pages_total + a.pages_per_split - 1) / a.pages_per_split;
     if (split > 0 && split >= live_splits) return;
 
-    const unsigned short* pool = static_cast<const unsigned short*>(st.pool);
-    PageRegs<D> buf[kPrefetch];
+    const void* pool = st.pool;
+    using Raw = std::conditional_t<kFp8, PageRegs8<D>, PageRegs<D>>;    // a page as it sits in the store
+    Raw buf[kPrefetch];
 #pragma unroll
     for (int j = 0; j < kPrefetch; ++j)
-        if (j < my_pages) load_page<D>(buf[j], pool, page_offset(st, slot, first_blk[j], g), lane);
+        if (j < my_pages) load_page(buf[j], pool, page_offset(st, slot, first_blk[j], g), lane);
 
     const float scale_log2 = 1.44269504088896340736f * (D == 128 ? 0.08838834764831845f : 0.125f);
     float m[NT], l[NT];
@@ -407,18 +455,25 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
         for (int jj = 0; jj < kPrefetch / 2; ++jj) {
             const int pr = p0 + jj;
             if (pr >= my_pairs) break;
-            PageRegs<D>& pa = buf[2 * jj];
-            PageRegs<D>& pb = buf[2 * jj + 1];
+            Raw& pa = buf[2 * jj];
+            Raw& pb = buf[2 * jj + 1];
             const int ka = 2 * pr, kb = ka + 1;
             const bool have_b = kb < my_pages;
             const int page_a = my_first + ka * kWaves, page_b = my_first + kb * kWaves;
             const int tok_a = page_a * kPageTokens, tok_b = page_b * kPageTokens;
 
-            consume_pair<D, NT>(pa, pb, have_b, tok_a, tok_b, n_min, n_max, n_col, qf, m, l, o, quad, scale_log2);
+            if constexpr (kFp8) {
+                PageRegs<D> wa, wb;                                   // widened to bf16 operands
+                widen<D>(pa, wa);
+                widen<D>(pb, wb);                                     // an absent page is zeroed by consume_pair
+                consume_pair<D, NT>(wa, wb, have_b, tok_a, tok_b, n_min, n_max, n_col, qf, m, l, o, quad, scale_log2);
+            } else {
+                consume_pair<D, NT>(pa, pb, have_b, tok_a, tok_b, n_min, n_max, n_col, qf, m, l, o, quad, scale_log2);
+            }
             if (ka + kPrefetch < my_pages)
-                load_page<D>(pa, pool, page_offset(st, slot, safe_block_of(st, b, page_a + kPrefetch * kWaves), g), lane);
+                load_page(pa, pool, page_offset(st, slot, safe_block_of(st, b, page_a + kPrefetch * kWaves), g), lane);
             if (kb + kPrefetch < my_pages)
-                load_page<D>(pb, pool, page_offset(st, slot, safe_block_of(st, b, page_b + kPrefetch * kWaves), g), lane);
+                load_page(pb, pool, page_offset(st, slot, safe_block_of(st, b, page_b + kPrefetch * kWaves), g), lane);
         }
     }
 
@@ -678,19 +733,19 @@ void attn_bf16_wide_kernel(AttnArgs a)
     }
 }
 
-template <int D>
+template <int D, bool kFp8>
 int launch_bf16(const AttnArgs& a, hipStream_t s)
 {
     const int group = a.st.Hq / a.st.Hkv;
     if (a.T_new == 1) {
         dim3 grid(a.st.Hkv, a.B, a.n_splits);
-        hipLaunchKernelGGL((attn_bf16_kernel<D, 1, 4>), grid, dim3(kThreads), 0, s, a);
-    } else if (const int ncols = a.T_new * group; ncols >= 256 && (long)a.st.Hkv * a.B * ((ncols + 255) / 256) >= 256) {
+        hipLaunchKernelGGL((attn_bf16_kernel<D, 1, 4, kFp8>), grid, dim3(kThreads), 0, s, a);
+    } else if (const int ncols = a.T_new * group; !kFp8 && ncols >= 256 && (long)a.st.Hkv * a.B * ((ncols + 255) / 256) >= 256) {
         // Enough columns per (sequence, kv head) to share every page among eight wavefronts, and
         // enough such workgroups to cover the chip without splitting the context.
         dim3 grid(a.st.Hkv, a.B, (ncols + 255) / 256);
         hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8>), grid, dim3(512), 0, s, a);
-    } else if (ncols >= 64 && (long)a.st.Hkv * a.B * ((ncols + 63) / 64) >= 512) {
+    } else if (!kFp8 && ncols >= 64 && (long)a.st.Hkv * a.B * ((ncols + 63) / 64) >= 512) {
         // Fewer columns: 16 per wavefront, four wavefronts; small enough in registers for several
         // workgroups per compute unit to hide each other's softmax arithmetic.
         dim3 grid(a.st.Hkv, a.B, (ncols + 63) / 64);
@@ -698,7 +753,7 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
     } else {
         const int cgroups = (a.T_new * group + 63) / 64;
         dim3 grid(a.st.Hkv, a.B, a.n_splits * cgroups);
-        hipLaunchKernelGGL((attn_bf16_kernel<D, 4, 2>), grid, dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((attn_bf16_kernel<D, 4, 2, kFp8>), grid, dim3(kThreads), 0, s, a);
     }
     if (hipError_t e = hipGetLastError()) return (int)e;
     return 0;
@@ -714,7 +769,8 @@ int launch_attention(const AttnArgs& a, void* stream)
         hipLaunchKernelGGL(attn_f32_kernel, grid, dim3(64), 0, s, a);
         return (int)hipGetLastError();
     }
-    return a.st.head_dim == 128 ? launch_bf16<128>(a, s) : launch_bf16<64>(a, s);
+    if (a.st.dtype == 2) return a.st.head_dim == 128 ? launch_bf16<128, true>(a, s) : launch_bf16<64, true>(a, s);
+    return a.st.head_dim == 128 ? launch_bf16<128, false>(a, s) : launch_bf16<64, false>(a, s);
 }
 
 const char* hip_error_string(int err) { return hipGetErrorString(static_cast<hipError_t>(err)); }

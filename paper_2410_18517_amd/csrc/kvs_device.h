@@ -50,5 +50,45 @@ __device__ __forceinline__ int v_index_bf16(int t, int c)
     return ((((c >> 5) * 4 + (t >> 2)) * 16 + (c & 15)) * 2 + ((c >> 4) & 1)) * 4 + (t & 3);
 }
 
+// The same for the fp8 store (one byte per element).  A lane's 16-byte load covers two 32-deep
+// contraction steps of K (8 channels each), or four 16-channel tiles of V (4 tokens each).
+__device__ __forceinline__ int k_index_fp8(int t, int c)
+{
+    return ((((c >> 6) * 4 + ((c & 31) >> 3)) * 16 + t) * 16) + ((c >> 5) & 1) * 8 + (c & 7);
+}
+__device__ __forceinline__ int v_index_fp8(int t, int c)
+{
+    return ((((c >> 6) * 4 + (t >> 2)) * 16 + (c & 15)) * 16) + ((c >> 4) & 3) * 4 + (t & 3);
+}
+
+// bf16 bit pattern -> E4M3 code: round to nearest, ties to even, saturating at +-448; NaN -> NaN.
+// Integer arithmetic on the bit pattern (exponent rebias 127 -> 7 is -120; 7 -> 3 mantissa bits),
+// so the result does not depend on any conversion instruction's mode.
+__device__ __forceinline__ unsigned bf16_to_e4m3(unsigned h)
+{
+    const unsigned sign = (h >> 8) & 0x80u, mag = h & 0x7fffu;
+    if (mag > 0x7f80u) return sign | 0x7fu;                       // NaN
+    if (mag >= 0x43e0u) return sign | 0x7eu;                      // >= 448 (and infinity): saturate
+    if (mag >= (121u << 7)) {                                     // >= 2^-6: normal in the target
+        const unsigned r = (mag + 7u + ((mag >> 4) & 1u)) >> 4;   // drop 4 mantissa bits, nearest even; may carry
+        return sign | (r - (120u << 3));
+    }
+    // below 2^-6 the target is m * 2^-9, m = 0..8 (8 is the code of 2^-6 itself)
+    const float f = __uint_as_float(mag << 16) * 512.f;
+    return sign | (unsigned)__builtin_rintf(f);
+}
+
+// E4M3 code -> bf16 bit pattern (exact).
+__device__ __forceinline__ unsigned e4m3_to_bf16(unsigned b)
+{
+    const unsigned sign = (b & 0x80u) << 8, em = b & 0x7fu;
+    if (em == 0x7fu) return sign | 0x7fc0u;
+    const unsigned e = em >> 3, m = em & 7u;
+    if (e) return sign | ((e + 120u) << 7) | (m << 4);
+    if (!m) return sign;
+    const unsigned p = 31u - __builtin_clz(m);                    // m * 2^-9 = 2^(p-9) * (m / 2^p)
+    return sign | ((p + 118u) << 7) | ((m << (7u - p)) & 0x7fu);
+}
+
 }  // namespace
 }  // namespace kvs

@@ -49,11 +49,11 @@ int check_desc(const kvs_desc* d)
         return fail(KVS_ERR_INVALID_ARG, "num_blocks and max_blocks_per_seq must be positive");
     if (d->max_blocks_per_seq > (1 << 26))
         return fail(KVS_ERR_CAPACITY, "max_blocks_per_seq too large");
-    if (d->dtype == KVS_BF16) {
+    if (d->dtype == KVS_BF16 || d->dtype == KVS_FP8) {
         if (d->head_dim != 128 && d->head_dim != 64)
-            return fail(KVS_ERR_UNSUPPORTED, "bf16 store supports head_dim 64 or 128 (got %d)", d->head_dim);
+            return fail(KVS_ERR_UNSUPPORTED, "bf16 and fp8 stores support head_dim 64 or 128 (got %d)", d->head_dim);
         if (d->Hq / d->Hkv > 16)
-            return fail(KVS_ERR_UNSUPPORTED, "bf16 store supports at most 16 query heads per kv head");
+            return fail(KVS_ERR_UNSUPPORTED, "bf16 and fp8 stores support at most 16 query heads per kv head");
     } else if (d->dtype == KVS_F32) {
         if (d->head_dim <= 0 || d->head_dim % 64 != 0 || d->head_dim > 256)
             return fail(KVS_ERR_UNSUPPORTED, "fp32 store supports head_dim 64, 128, 192 or 256 (got %d)", d->head_dim);
@@ -63,7 +63,7 @@ int check_desc(const kvs_desc* d)
     return KVS_OK;
 }
 
-size_t elem_bytes(int dtype) { return dtype == KVS_BF16 ? 2 : 4; }
+size_t elem_bytes(int dtype) { return dtype == KVS_BF16 ? 2 : (dtype == KVS_FP8 ? 1 : 4); }
 
 int check_map(const int32_t* m, int L)
 {
@@ -316,6 +316,7 @@ int kvs_compact_kv(const kvs_store* store, int layer, const int32_t* keep_idx, c
     if (!store->block_table && (long)B * store->desc.max_blocks_per_seq > store->desc.num_blocks)
         return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
     if (B > 65535) return fail(KVS_ERR_CAPACITY, "B is limited to 65535");
+    if (store->desc.dtype == KVS_FP8) return fail(KVS_ERR_UNSUPPORTED, "compaction of fp8 slots is not implemented");
     if (store->host_share_map[layer] != layer) return KVS_NOOP;   // its donor's compaction is the one it reads
     kvs::CompactArgs a;
     a.st = view_of(store, layer);

@@ -17,7 +17,7 @@ __global__ void copy_rows_kernel(CopyArgs a)
 {
     const StoreView& st = a.st;
     const int D = st.head_dim;
-    const int per = st.dtype == 1 ? 8 : 4;
+    const int per = st.dtype == 0 ? 4 : 8;       // rows are bf16 for the bf16 and fp8 stores, fp32 for the fp32 store
     const int chunks = D / per;
     const long total = (long)a.B * a.T * st.Hkv * chunks;
     const long tid = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -34,7 +34,40 @@ __global__ void copy_rows_kernel(CopyArgs a)
     const int t = (int)(pos % kPageTokens);
     const size_t page = page_offset(st, slot, blk, g);
     const size_t row = (((size_t)b * a.T + i) * st.Hkv + g) * D + (size_t)ch * per;
-    if (st.dtype == 1) {
+    if (st.dtype == 2) {
+        // fp8 store: 8 channels of a row are 8 bytes of the K page (one store) and 8 single bytes of
+        // the V page; quantisation and its inverse are the integer routines of kvs_device.h
+        unsigned char* kp = static_cast<unsigned char*>(st.pool) + page;
+        unsigned char* vp = kp + kPageTokens * D;
+        unsigned short* kr = static_cast<unsigned short*>(a.k) + row;
+        unsigned short* vr = static_cast<unsigned short*>(a.v) + row;
+        const int c0 = ch * 8;
+        if (kToStore) {
+            const uint4 kk = *reinterpret_cast<const uint4*>(kr), vv = *reinterpret_cast<const uint4*>(vr);
+            const unsigned kw[4] = {kk.x, kk.y, kk.z, kk.w}, vw[4] = {vv.x, vv.y, vv.z, vv.w};
+            unsigned lo = 0, hi = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                lo |= bf16_to_e4m3((kw[e >> 1] >> ((e & 1) * 16)) & 0xffffu) << (8 * e);
+                hi |= bf16_to_e4m3((kw[2 + (e >> 1)] >> ((e & 1) * 16)) & 0xffffu) << (8 * e);
+            }
+            *reinterpret_cast<uint2*>(kp + k_index_fp8(t, c0)) = make_uint2(lo, hi);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                vp[v_index_fp8(t, c0 + e)] = (unsigned char)bf16_to_e4m3((vw[e >> 1] >> ((e & 1) * 16)) & 0xffffu);
+        } else {
+            const uint2 kb = *reinterpret_cast<const uint2*>(kp + k_index_fp8(t, c0));
+            unsigned kw[4] = {0, 0, 0, 0}, vw[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned kbyte = ((e < 4 ? kb.x : kb.y) >> (8 * (e & 3))) & 0xffu;
+                kw[e >> 1] |= e4m3_to_bf16(kbyte) << ((e & 1) * 16);
+                vw[e >> 1] |= e4m3_to_bf16(vp[v_index_fp8(t, c0 + e)]) << ((e & 1) * 16);
+            }
+            *reinterpret_cast<uint4*>(kr) = make_uint4(kw[0], kw[1], kw[2], kw[3]);
+            *reinterpret_cast<uint4*>(vr) = make_uint4(vw[0], vw[1], vw[2], vw[3]);
+        }
+    } else if (st.dtype == 1) {
         unsigned short* pool = static_cast<unsigned short*>(st.pool);
         unsigned short* kp = pool + page;
         unsigned short* vp = kp + kPageTokens * D;
@@ -208,7 +241,7 @@ int launch_append(const CopyArgs& a, void* stream)
                            static_cast<hipStream_t>(stream), a);
         return (int)hipGetLastError();
     }
-    const int per = a.st.dtype == 1 ? 8 : 4;
+    const int per = a.st.dtype == 0 ? 4 : 8;
     const long total = (long)a.B * a.T * a.st.Hkv * (a.st.head_dim / per);
     const unsigned blocks = (unsigned)((total + 255) / 256);
     hipLaunchKernelGGL(copy_rows_kernel<true>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), a);
@@ -228,7 +261,7 @@ int launch_compact(const CompactArgs& a, void* stream)
 
 int launch_gather(const CopyArgs& a, void* stream)
 {
-    const int per = a.st.dtype == 1 ? 8 : 4;
+    const int per = a.st.dtype == 0 ? 4 : 8;
     const long total = (long)a.B * a.T * a.st.Hkv * (a.st.head_dim / per);
     const unsigned blocks = (unsigned)((total + 255) / 256);
     hipLaunchKernelGGL(copy_rows_kernel<false>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), a);

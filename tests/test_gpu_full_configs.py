@@ -122,3 +122,23 @@ def test_whole_prompt_prefill_full_size_sampled(kb):
                 want = orc.shared_attention(layer, share, _sub(case, case.K, b), _sub(case, case.V, b),
                                             inputs.to_oracle_array(q[b:b + 1, r0:r0 + 16]), np.array([r0], np.int32))
                 assert rel_l2_rows(got[b:b + 1, r0:r0 + 16], want).max() <= REL_L2_ATTENTION, (layer, b, r0)
+
+
+def test_decode_full_size_fp8_slots(kb):
+    """The 32k GQA workload with its slots kept in fp8: same launch configuration as the bf16 run,
+    half the bytes; sampled sequences, all heads, against the oracle on the values as stored."""
+    w = inputs.WORKLOADS["llama3-8b-32k"]
+    share = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)
+    lens = inputs.make_seq_lens(w, 1)
+    layers, fill = _sample_layers(share)
+    case = Case(kb, w.L, w.Hq, w.Hkv, w.d, w.B, "fp8", w.context, share, paged=True, seed=101,
+                fill_layers=fill, spare_blocks=0)
+    assert case.store.pool.numel() * 2 == (w.L - w.n_shared) * w.B * w.context * w.Hkv * w.d * 2 * 2
+    for layer in layers:
+        q = case.q(layer)
+        got = kb.kvs_decode_attention(case.store, layer, q.cuda(), lens).cpu().numpy()
+        assert np.isfinite(got).all()
+        for b in (0, w.B - 1):
+            want = orc.decode_attention(layer, share, _sub(case, case.K, b), _sub(case, case.V, b),
+                                        inputs.to_oracle_array(q[b:b + 1]), lens[b:b + 1])
+            assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, (layer, b)
