@@ -182,13 +182,13 @@ __device__ __forceinline__ void widen(const PageRegs8<D>& r, PageRegs<D>& o)
 // Zero the values of tokens `first`.. of this lane's four (first <= 0 clears all four): the
 // lane holds tokens 4*quad..4*quad+3 of the page, two per 32-bit word, for two channel tiles.
 template <int D>
-__device__ __forceinline__ void clear_values_from(PageRegs<D>& r, int first)
+__device__ __forceinline__ void clear_values_from(u32x4 (&v)[D / 32], int first)
 {
     const unsigned m01 = (0 < first ? 0x0000ffffu : 0u) | (1 < first ? 0xffff0000u : 0u);
     const unsigned m23 = (2 < first ? 0x0000ffffu : 0u) | (3 < first ? 0xffff0000u : 0u);
 #pragma unroll
     for (int s = 0; s < D / 32; ++s) {
-        r.v[s].x &= m01; r.v[s].y &= m23; r.v[s].z &= m01; r.v[s].w &= m23;
+        v[s].x &= m01; v[s].y &= m23; v[s].z &= m01; v[s].w &= m23;
     }
 }
 
@@ -236,40 +236,42 @@ __device__ __forceinline__ float column_sum(float x)
 }
 
 // One softmax / accumulation step over a pair of pages (32 tokens) for the NT column tiles of a
-// wavefront: pa and pb hold the pages' operands (pb absent: have_b false), tok_a / tok_b are
-// their first token positions, n_col[ct] the number of keys the lane's column of tile ct sees,
-// n_min / n_max the fewest / most keys any column of the wavefront sees.
+// wavefront, in three parts so that a caller whose pages sit in LDS can fetch the value operands
+// while the scores are being turned into probabilities.  ka / kb and va / vb hold the key and
+// value operands of the two pages (second page absent: have_b false), tok_a / tok_b are their
+// first token positions, n_col[ct] the number of keys the lane's column of tile ct sees, n_min /
+// n_max the fewest / most keys any column of the wavefront sees.
+//
+// Scores of the 32 tokens against the wavefront's columns: sa / sb, one accumulator per page and tile.
 template <int D, int NT>
-__device__ __forceinline__ void consume_pair(PageRegs<D>& pa, PageRegs<D>& pb, bool have_b, int tok_a, int tok_b,
-                                             int n_min, int n_max, const int (&n_col)[NT],
-                                             const bf16x8 (&qf)[NT][D / 32], float (&m)[NT], float (&l)[NT],
-                                             floatx4 (&o)[NT][D / 16], int quad, float scale_log2)
+__device__ __forceinline__ void pair_qk(const u32x4 (&ka)[D / 32], u32x4 (&kb)[D / 32], bool have_b,
+                                        const bf16x8 (&qf)[NT][D / 32], floatx4 (&sa)[NT], floatx4 (&sb)[NT])
 {
-    constexpr int KS = D / 32, DT = D / 16;
-    // tokens past the stored length hold whatever the allocation held: clear their
-    // values so a zero probability cannot meet a NaN
-    if (tok_a + kPageTokens > n_max) clear_values_from<D>(pa, n_max - tok_a - quad * 4);
+    constexpr int KS = D / 32;
     if (!have_b) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s) pb.k[s] = pb.v[s] = u32x4{0u, 0u, 0u, 0u};
-    } else if (tok_b + kPageTokens > n_max) {
-        clear_values_from<D>(pb, n_max - tok_b - quad * 4);
+        for (int s = 0; s < KS; ++s) kb[s] = u32x4{0u, 0u, 0u, 0u};
     }
-    const bool need_mask = !have_b || tok_b + kPageTokens > n_min || tok_a + kPageTokens > n_min;
-
-    floatx4 sa[NT], sb[NT];
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) sa[ct] = sb[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s)
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
-            sa[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa.k[s]), qf[ct][s],
-                                                             sa[ct], 0, 0, 0);
-            sb[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pb.k[s]), qf[ct][s],
-                                                             sb[ct], 0, 0, 0);
+            sa[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[s]), qf[ct][s], sa[ct], 0, 0, 0);
+            sb[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[s]), qf[ct][s], sb[ct], 0, 0, 0);
         }
-    bf16x8 pf[NT];
+}
+
+// Masking, the softmax update of m, l and o, and the probabilities as bf16 operands.
+template <int D, int NT>
+__device__ __forceinline__ void pair_softmax(const floatx4 (&sa)[NT], const floatx4 (&sb)[NT], bool have_b, int tok_a,
+                                             int tok_b, int n_min, const int (&n_col)[NT], float (&m)[NT],
+                                             float (&l)[NT], floatx4 (&o)[NT][D / 16], int quad, float scale_log2,
+                                             bf16x8 (&pf)[NT])
+{
+    constexpr int DT = D / 16;
+    const bool need_mask = !have_b || tok_b + kPageTokens > n_min || tok_a + kPageTokens > n_min;
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) {
         float z[8];                                          // raw scores; the scale is applied inside the exponent
@@ -310,16 +312,45 @@ __device__ __forceinline__ void consume_pair(PageRegs<D>& pa, PageRegs<D>& pb, b
                                     pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
         pf[ct] = __builtin_bit_cast(bf16x8, pw);
     }
+}
+
+// o += V^T . P^T.  Tokens past the stored length hold whatever the allocation held:
+// their values are cleared first, so that a zero probability cannot meet a NaN.
+template <int D, int NT>
+__device__ __forceinline__ void pair_values(u32x4 (&va)[D / 32], u32x4 (&vb)[D / 32], bool have_b, int tok_a, int tok_b,
+                                            int n_max, int quad, const bf16x8 (&pf)[NT], floatx4 (&o)[NT][D / 16])
+{
+    constexpr int KS = D / 32, DT = D / 16;
+    if (tok_a + kPageTokens > n_max) clear_values_from<D>(va, n_max - tok_a - quad * 4);
+    if (!have_b) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) vb[s] = u32x4{0u, 0u, 0u, 0u};
+    } else if (tok_b + kPageTokens > n_max) {
+        clear_values_from<D>(vb, n_max - tok_b - quad * 4);
+    }
 #pragma unroll
     for (int c = 0; c < DT; ++c) {
-        const u32x4 va = pa.v[c >> 1], vb = pb.v[c >> 1];
+        const u32x4 xa = va[c >> 1], xb = vb[c >> 1];
         // contraction slots 0-3: tokens 4*quad.. of the first page, 4-7: of the second
-        const u32x4 vcat = (c & 1) ? u32x4{va.z, va.w, vb.z, vb.w} : u32x4{va.x, va.y, vb.x, vb.y};
+        const u32x4 vcat = (c & 1) ? u32x4{xa.z, xa.w, xb.z, xb.w} : u32x4{xa.x, xa.y, xb.x, xb.y};
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct)
             o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vcat), pf[ct],
                                                                o[ct][c], 0, 0, 0);
     }
+}
+
+template <int D, int NT>
+__device__ __forceinline__ void consume_pair(PageRegs<D>& pa, PageRegs<D>& pb, bool have_b, int tok_a, int tok_b,
+                                             int n_min, int n_max, const int (&n_col)[NT],
+                                             const bf16x8 (&qf)[NT][D / 32], float (&m)[NT], float (&l)[NT],
+                                             floatx4 (&o)[NT][D / 16], int quad, float scale_log2)
+{
+    floatx4 sa[NT], sb[NT];
+    bf16x8 pf[NT];
+    pair_qk<D, NT>(pa.k, pb.k, have_b, qf, sa, sb);
+    pair_softmax<D, NT>(sa, sb, have_b, tok_a, tok_b, n_min, n_col, m, l, o, quad, scale_log2, pf);
+    pair_values<D, NT>(pa.v, pb.v, have_b, tok_a, tok_b, n_max, quad, pf, o);
 }
 
 template <int D, int NT, int kPrefetch, bool kFp8>
@@ -699,15 +730,24 @@ void attn_bf16_wide_kernel(AttnArgs a)
                 const int tok_a = 2 * pair * kPageTokens, tok_b = tok_a + kPageTokens;
                 if (tok_a < n_max) {
                     const bool have_b = 2 * pair + 1 < my_pages;
-                    PageRegs<D> pa, pb;
+                    // keys first; the value operands are fetched from LDS once the score products are
+                    // issued, into the registers the keys no longer need
+                    u32x4 ka[KS], kb[KS], va[KS], vb[KS];
 #pragma unroll
                     for (int s = 0; s < KS; ++s) {
-                        pa.k[s] = tile[buf][s * 64 + lane];
-                        pa.v[s] = tile[buf][(KS + s) * 64 + lane];
-                        pb.k[s] = have_b ? tile[buf][kPageVecs + s * 64 + lane] : u32x4{0u, 0u, 0u, 0u};
-                        pb.v[s] = have_b ? tile[buf][kPageVecs + (KS + s) * 64 + lane] : u32x4{0u, 0u, 0u, 0u};
+                        ka[s] = tile[buf][s * 64 + lane];
+                        kb[s] = tile[buf][kPageVecs + s * 64 + lane];       // an absent second page is zeroed below
                     }
-                    consume_pair<D, NT>(pa, pb, have_b, tok_a, tok_b, n_min, n_max, n_col, qf, m, l, o, quad, scale_log2);
+                    floatx4 sa[NT], sb[NT];
+                    bf16x8 pf[NT];
+                    pair_qk<D, NT>(ka, kb, have_b, qf, sa, sb);
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) {                         // travel under the softmax arithmetic
+                        va[s] = tile[buf][(KS + s) * 64 + lane];
+                        vb[s] = tile[buf][kPageVecs + (KS + s) * 64 + lane];
+                    }
+                    pair_softmax<D, NT>(sa, sb, have_b, tok_a, tok_b, n_min, n_col, m, l, o, quad, scale_log2, pf);
+                    pair_values<D, NT>(va, vb, have_b, tok_a, tok_b, n_max, quad, pf, o);
                 }
                 if (pair + 1 < wg_pairs) {
                     KVS_PUT_PAIR(buf ^ 1, (j + 1) % kDepth)            // that buffer was last read before the previous barrier
