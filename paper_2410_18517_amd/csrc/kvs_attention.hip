@@ -288,25 +288,28 @@ __device__ __forceinline__ void pair_softmax(const floatx4 (&sa)[NT], const floa
                 z[4 + i] = (have_b && tb + i < n_col[ct]) ? z[4 + i] : -INFINITY;
             }
         }
-        const float mx = scale_log2 * column_max(fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
-                                                       fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7]))));
         // m is the reference of the exponentials, not necessarily the running maximum:
         // softmax is shift invariant, so the reference only moves (and o, l are only
         // rescaled) when a score exceeds it by more than kRefSlack; until then weights
         // may reach 2^kRefSlack, which fp32 sums and bf16 operands hold without loss.
-        const bool up = mx > m[ct] + kRefSlack;              // false while everything is masked
-        const float m_new = up ? mx : m[ct];
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;   // column sees nothing yet
-        float p[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(z[i], scale_log2, -m_use));
-        if (__any(up)) {
-            const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_use);   // 1 in lanes that keep their reference
+        // Whether any column must move is decided from the lanes' own maxima; the reduction
+        // over the four lanes of a column is only paid for on the pairs where one does.
+        const float lane_max = scale_log2 * fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
+                                                  fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+        if (__any(lane_max > m[ct] + kRefSlack)) {           // false while everything is masked
+            const float mx = column_max(lane_max);
+            const bool up = mx > m[ct] + kRefSlack;
+            const float m_new = up ? mx : m[ct];
+            const float alpha = __builtin_amdgcn_exp2f(m[ct] - (m_new == -INFINITY ? 0.f : m_new));   // 1 in lanes that keep their reference
             l[ct] *= alpha;
 #pragma unroll
             for (int c = 0; c < DT; ++c) o[ct][c] *= alpha;
             m[ct] = m_new;
         }
+        const float m_use = m[ct] == -INFINITY ? 0.f : m[ct];   // column sees nothing yet
+        float p[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(z[i], scale_log2, -m_use));
         l[ct] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
         const uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
                                     pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
