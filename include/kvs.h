@@ -88,7 +88,7 @@ typedef int (*kvs_accept_fn)(const int32_t* candidate_share_map, int L, void* us
  *   accept          NULL accepts every candidate
  *   share_map, slot_of_layer   host, out[L];  n_slots, n_shared   host, out
  * Returns KVS_OK, or KVS_ERR_TARGET_UNREACHED with the partial strategy in the outputs
- * when the ranking is exhausted first (the paper's "return None").
+ * when the ranking is exhausted first (the search then reports that it found no strategy).
  * The random-sharing baseline (Sec. 5.2, random pairs at a fixed compression rate) is the same
  * walk over a ranking drawn at random: pass a matrix of independent random values, accept = NULL.
  */
@@ -149,7 +149,7 @@ int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const vo
 
 /*
  * Key/value projection fused with the append: the computation a sharing strategy removes for
- * every layer that reads a donor's cache (Sec. 3.2; the abstract's "KV cache computation").
+ * every layer that reads a donor's cache (Sec. 3.2; the cache computation the abstract counts as saved).
  * For a layer that keeps its own cache, with x device [B][T_new][hidden] and the projection
  * weights w_k, w_v device [Hkv*head_dim][hidden] (row = output channel, bf16):
  *     k = x . w_k^T,   v = x . w_v^T                      (fp32 accumulation)
@@ -257,14 +257,14 @@ int kvs_set_split_tokens(int tokens);
 /* ---------------------------------------------------------------- calibration distance */
 
 /*
- * Layer-dissimilarity matrix of the strategy search (Sec. 3.1.2, Algorithm 1 first step).
+ * Layer-dissimilarity matrix of the strategy search (Sec. 3.1.2, Algorithm 1).
  * kv_samples: device [S][L][2][N] of `dtype`: calibration sample, layer, keys(0)/values(1),
  * flattened [Hkv][T][head_dim] index; all samples have the same length.  The keys and the
  * values of a layer are averaged over the S samples, and
  *   dK2[a][b] = || meanK_a - meanK_b ||^2,  dV2 likewise,  D[a][b] = sqrt(dK2 + dV2)
  * i.e. the Euclidean distance between the flattened [mean K ; mean V] vectors.  Outputs are
  * device fp32 [L][L], symmetric with a zero diagonal; dK2 and dV2 are returned so that other
- * readings of "average the keys and values separately" can be formed by the caller.
+ * readings of the paper's separate averaging of keys and values can be formed by the caller.
  * Supported: L <= 64.  workspace >= kvs_distance_workspace_bytes(L).
  */
 int kvs_layer_distance(const void* kv_samples, int S, int L, size_t N, int dtype,
@@ -281,7 +281,7 @@ size_t kvs_distance_workspace_bytes(int L);
  * and of the original model on the calibration set, device [S][N] of `dtype` (S sentences of
  * equal length, N = tokens x hidden size, flattened).  *similarity (device, one float):
  *   mode 0: cosine similarity of the two sentence-averaged vectors (the text of Sec. 3.1.2:
- *           "average these representations across different sentences", then the cosine);
+ *           the representations are averaged over the sentences first, then one cosine);
  *   mode 1: average over the sentences of the per-sentence cosine (the procedure's name).
  * A zero vector contributes a cosine of 0.  The caller compares the result with the
  * threshold T inside its kvs_accept_fn (keep the pair iff similarity > T).

@@ -14,7 +14,7 @@
  *     definition: z_j = q.k_j / sqrt(d), p = softmax(z), out = sum_j p_j v_j, with
  *     grouped-query head mapping g = h / (Hq / Hkv).
  *   - The layer representation and distance of the strategy search (paper Sec. 3.1.2,
- *     "KV Cache Similarity Calculation", and Algorithm 1, first step): per layer the
+ *     "KV Cache Similarity Calculation", and Algorithm 1): per layer the
  *     keys and the values are averaged over the calibration samples, flattened, and the
  *     Euclidean distance between two layers is taken over the concatenated
  *     [mean K ; mean V] vector.
@@ -157,7 +157,7 @@ int orc_shared_attention(int layer, const int32_t* share_map, int L,
 }
 
 /*
- * Layer dissimilarity (paper Sec. 3.1.2 / Algorithm 1 first step).
+ * Layer dissimilarity (paper Sec. 3.1.2 / Algorithm 1).
  *   kv   [S][L][2][N]   calibration caches: sample, layer, (0 = keys, 1 = values),
  *                       flattened [Hkv][T][d] index
  *   dK2, dV2, D  [L][L] (double):  dK2[a][b] = || meanK_a - meanK_b ||^2, dV2 likewise,

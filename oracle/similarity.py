@@ -3,7 +3,7 @@
 Test infrastructure only.  hidden_shared, hidden_original: [S, N] arrays (float32, or uint16
 holding bf16 bits), one flattened last-layer hidden state per calibration sentence.
   mode 0: the representations are averaged over the sentences, then one cosine is taken
-          (the text: "average these representations across different sentences");
+          (the text of Sec. 3.1.2);
   mode 1: one cosine per sentence, averaged (the procedure's name).
 A zero vector is given a cosine of 0.  Everything in float64.
 """

@@ -1,5 +1,5 @@
-// Layer-dissimilarity matrix of the strategy search (paper Sec. 3.1.2, Algorithm 1 first
-// step) on gfx950: per layer, keys and values are averaged over the calibration samples and
+// Layer-dissimilarity matrix of the strategy search (paper Sec. 3.1.2, Algorithm 1) on
+// gfx950: per layer, keys and values are averaged over the calibration samples and
 // the squared Euclidean distance of every layer pair is accumulated, keys and values apart.
 //
 // One pass over the samples: a workgroup takes chunks of kChunk consecutive positions of the

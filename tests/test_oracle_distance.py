@@ -1,4 +1,4 @@
-"""Pins of the layer-distance oracle (paper Sec. 3.1.2, Algorithm 1 first step).
+"""Pins of the layer-distance oracle (paper Sec. 3.1.2, Algorithm 1).
 
 Closed forms, metric axioms and torch.cdist (the library routine the one-sample case reduces
 to) fix: mean over samples taken before the distance, keys and values both counted,
