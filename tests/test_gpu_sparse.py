@@ -164,3 +164,28 @@ def test_several_rows_per_head_cross_pages(kb):
             untouched = [t for t in range(40) if not p <= t < p + 21]
             assert np.array_equal(k[b, untouched, h], case.K[0][b, untouched, h])
             assert np.array_equal(v[b, untouched, h], case.V[0][b, untouched, h])
+
+
+def test_compaction_and_per_head_calls_stay_inside_the_store_on_bad_input(kb):
+    """Keep lists are the caller's; the kernels clamp what they are given instead of trusting it:
+    positions outside the sequence, counts outside [0, max_keep] and lengths beyond the capacity
+    neither fault nor touch another slot."""
+    L, Hq, Hkv, d, B, cap, T = 2, 4, 2, 128, 2, 64, 64
+    share = np.array([0, 1], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, "bf16", cap, share, paged=True, seed=35, fill_tokens=T)
+    idx = np.array([[[-7, 3, 10 ** 9, 5, 2, 63, 64, 1 << 30]] * Hkv] * B, np.int32)
+    cnt = np.array([[100, -3], [8, 0]], np.int32)                      # beyond max_keep, negative, exact, empty
+    assert kb.kvs_compact_kv(case.store, 1, idx, cnt) == kb.KVS_OK
+    pos = np.array([[cap + 5, -1], [cap - 1, 10 ** 6]], np.int32)      # only (1, 0) is inside the capacity
+    k_new = inputs.normal((B, 2, Hkv, d), 35, 600)
+    assert kb.kvs_append_kv_per_head(case.store, 1, k_new.cuda(), k_new.cuda(), pos) == kb.KVS_OK
+    lens = np.array([[[10 ** 9, -4], [cap, 0]], [[10 ** 9, -4], [cap, 0]]], np.int32)
+    q = case.q(1)
+    out = kb.kvs_decode_attention_per_head(case.store, 1, q.cuda(), lens).cpu().numpy()
+    assert np.isfinite(out).all()
+    group = Hq // Hkv
+    assert np.all(out[:, group:] == 0)                                  # lengths <= 0: zero rows
+    k0, v0 = kb.kvs_gather_kv(case.store, 0, 0, T, B)                   # slot 0 never touched
+    assert np.array_equal(inputs.to_oracle_array(k0), case.K[0]) and np.array_equal(inputs.to_oracle_array(v0), case.V[0])
+    k1, _ = kb.kvs_gather_kv(case.store, 1, 0, cap, B)
+    assert np.array_equal(inputs.to_oracle_array(k1)[1, cap - 1, 0], inputs.to_oracle_array(k_new)[1, 0, 0])
