@@ -295,6 +295,8 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--two-calls", action="store_true",
+                    help="decode mode: kvs_append_kv + kvs_decode_attention per layer instead of kvs_decode_step")
     ap.add_argument("--store", choices=["fp8"], default=None,
                     help="decode mode: keep the slots in fp8 (E4M3) instead of the workload's type")
     ap.add_argument("--prefill-rows", type=int, default=0,
@@ -370,9 +372,14 @@ def main():
     torch.cuda.synchronize()
 
     def step():
+        # every layer: store this step's key/value row (layers that read a donor's cache store nothing)
+        # and attend; one launch per layer, or the two separate calls with --two-calls
         for l in range(w.L):
-            kb.kvs_append_kv(store, l, k_new, v_new, pos_dev)
-            kb.kvs_decode_attention(store, l, q[l], lens_dev, out=out[l], workspace=ws)
+            if args.two_calls:
+                kb.kvs_append_kv(store, l, k_new, v_new, pos_dev)
+                kb.kvs_decode_attention(store, l, q[l], lens_dev, out=out[l], workspace=ws)
+            else:
+                kb.kvs_decode_step(store, l, q[l], k_new, v_new, lens_dev, out=out[l], workspace=ws)
 
     if args.traffic_probe:
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)      # 1 GiB read, 1 GiB written
@@ -422,7 +429,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name if store_dtype == w.dtype else f"{w.name}, {store_dtype} slots", "layers": w.L, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "batch": w.B, "context": w.context if w.min_context is None else [w.min_context, w.context],
-                   "page_tokens": 16, "shared_layers": w.n_shared, "kv_slots": int(store.desc.n_slots)},
+                   "page_tokens": 16, "shared_layers": w.n_shared, "kv_slots": int(store.desc.n_slots),
+                   "step": "kvs_append_kv + kvs_decode_attention per layer" if args.two_calls
+                           else "kvs_decode_step per layer"},
         "hbm_gbps": round(alg_bytes * w.L / (ms_per_step * 1e-3) / 1e9, 1),
         "hbm_frac": round(alg_bytes * w.L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "roofline": roofline,

@@ -193,6 +193,22 @@ int kvs_decode_attention(const kvs_store* store, int layer, const void* q,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * One decode step in one launch: kvs_append_kv(k_new, v_new at position seq_lens[b] - 1) followed
+ * by kvs_decode_attention(q, seq_lens), for the layers that keep their own cache; for a layer
+ * that reads a donor's cache k_new and v_new are ignored and the call is kvs_decode_attention
+ * (its donor stored this step's token when its own turn came).  On a bf16 store the attention
+ * kernel takes the new token from k_new / v_new directly -- it joins the softmax in the merge of
+ * the context splits -- and writes it to its place in the store on the side, so no second launch
+ * and no wait for the write; on other store types the call is the two launches.
+ *   q device [B][Hq][head_dim], k_new, v_new device [B][1][Hkv][head_dim], all bf16 (fp32 for an
+ *   fp32 store);  seq_lens device [B], counting the new token;  out, workspace as
+ *   kvs_decode_attention.  Positions at or beyond the capacity are not stored.
+ */
+int kvs_decode_step(const kvs_store* store, int layer, const void* q, const void* k_new,
+                    const void* v_new, const int32_t* seq_lens, int B, float* out,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Causal attention of T_new new query rows per sequence (the prefill side of Sec. 3.2):
  * row i of sequence b sits at position start_pos[b] + i and sees keys 0..start_pos[b] + i of
  * the cache `layer` attends to, which must already hold them (append first; a recipient's

@@ -25,7 +25,7 @@ EXPORTS = [
     "kvs_decode_attention", "kvs_prefill_attention", "kvs_set_split_tokens",
     "kvs_layer_distance", "kvs_distance_workspace_bytes", "kvs_avg_cos_sim", "kvs_cos_sim_workspace_bytes",
     "kvs_project_append_kv", "kvs_project_workspace_bytes",
-    "kvs_compact_kv", "kvs_append_kv_per_head", "kvs_decode_attention_per_head",
+    "kvs_compact_kv", "kvs_append_kv_per_head", "kvs_decode_attention_per_head", "kvs_decode_step",
 ]
 
 
@@ -79,6 +79,8 @@ def lib():
         L.kvs_decode_attention.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvs_decode_attention_per_head.argtypes = L.kvs_decode_attention.argtypes
+        L.kvs_decode_step.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvs_prefill_attention.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                             C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvs_set_split_tokens.argtypes = [C.c_int]
@@ -296,6 +298,24 @@ def kvs_decode_attention(store: KVStore, layer, q, seq_lens, out=None, workspace
     ws = workspace if workspace is not None else store.workspace(B, 1)
     _check(lib().kvs_decode_attention(C.byref(store.c), int(layer), q.data_ptr(), sl.data_ptr(), B,
                                       out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def kvs_decode_step(store: KVStore, layer, q, k_new, v_new, seq_lens, out=None, workspace=None):
+    """Append of this step's token and decode attention in one call; seq_lens counts the new token."""
+    assert q.is_cuda and q.is_contiguous() and q.dtype == store.torch_dtype
+    B = q.shape[0]
+    assert tuple(q.shape) == (B, store.desc.Hq, store.desc.head_dim)
+    for t in (k_new, v_new):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == store.torch_dtype
+        assert tuple(t.shape) == (B, 1, store.desc.Hkv, store.desc.head_dim)
+    sl = _dev_i32(seq_lens, store.device)
+    assert sl.numel() == B
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=store.device)
+    ws = workspace if workspace is not None else store.workspace(B, 1)
+    _check(lib().kvs_decode_step(C.byref(store.c), int(layer), q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                 sl.data_ptr(), B, out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
     return out
 
 

@@ -437,8 +437,15 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     const int slot_raw = donor < 56 ? __builtin_amdgcn_readlane(looked, 8 + donor) : st.slot_of_layer[donor];
     const int slot = slot_raw < 0 ? 0 : (slot_raw >= st.n_slots ? st.n_slots - 1 : slot_raw);
 
+    // A decode step that carries its own new token (k_new, v_new): the pages hold the tokens before
+    // it, the token itself joins the softmax in the merge below (split 0) and is written to its
+    // place in the store on the side -- no separate append launch, and nothing here waits for the write.
+    const bool carries_new = NT == 1 && !kFp8 && a.k_new != nullptr;
+    const int new_pos = len_raw - 1;
+    const bool has_new = carries_new && new_pos >= 0 && new_pos < cap;
+
     // keys visible to query row 0; row r sees n0 + r
-    int n0 = len_raw + a.lens_bias;
+    int n0 = len_raw + a.lens_bias - (carries_new ? 1 : 0);
     n0 = n0 < 0 ? 0 : n0;
     if (n0 > cap - (a.T_new - 1)) n0 = cap - (a.T_new - 1);
     int n_col[NT];
@@ -511,6 +518,38 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
         }
     }
 
+    __shared__ float lds_new_score[16];               // log2-domain score of the step's own token, per column
+    const bool adds_new = has_new && split == 0;
+    if (adds_new) {
+        const unsigned short* k_row = static_cast<const unsigned short*>(a.k_new) + ((size_t)b * st.Hkv + g) * D;
+        const unsigned short* v_row = static_cast<const unsigned short*>(a.v_new) + ((size_t)b * st.Hkv + g) * D;
+        // its place in the store, for the steps to come (this launch masks that position)
+        const int blk = block_of(st, b, new_pos / kPageTokens);
+        if (blk >= 0 && blk < st.num_blocks) {
+            unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, slot, blk, g);
+            unsigned short* vp = kp + kPageTokens * D;
+            const int t = new_pos % kPageTokens;
+            if ((int)threadIdx.x < D / 8)
+                *reinterpret_cast<uint4*>(kp + k_index_bf16(t, threadIdx.x * 8)) =
+                    *reinterpret_cast<const uint4*>(k_row + threadIdx.x * 8);
+            if ((int)threadIdx.x < D) vp[v_index_bf16(t, threadIdx.x)] = v_row[threadIdx.x];
+        }
+        // q . k_new for the 16 columns: a wavefront takes four columns, sixteen lanes each
+        constexpr int CH = D / 16;
+        const int cc = wave * 4 + quad, part = col;
+        float dot = 0.f;
+        if (cc < ncols) {
+            const unsigned short* qr = qbase + (((size_t)b * a.T_new) * st.Hq + g * group + cc) * D + part * CH;
+#pragma unroll
+            for (int e = 0; e < CH; ++e)
+                dot += __uint_as_float((unsigned)qr[e] << 16) * __uint_as_float((unsigned)k_row[part * CH + e] << 16);
+        }
+#pragma unroll
+        for (int o_ = 8; o_ > 0; o_ >>= 1) dot += __shfl_xor(dot, o_);
+        const float scale = 1.44269504088896340736f * (D == 128 ? 0.08838834764831845f : 0.125f);
+        if (part == 0) lds_new_score[cc] = cc < ncols ? dot * scale : -INFINITY;   // read after the merge's barrier
+    }
+
     // merge the four wavefront states, one column tile at a time
     __shared__ float lds_o[kWaves][16][D + 4];
     __shared__ float lds_m[kWaves][16];
@@ -535,9 +574,18 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             float mw[kWaves], M = -INFINITY;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) { mw[w] = lds_m[w][cc]; M = fmaxf(M, mw[w]); }
+            const float m_new_tok = adds_new ? lds_new_score[cc] : -INFINITY;
+            M = fmaxf(M, m_new_tok);
             const float M_use = M == -INFINITY ? 0.f : M;
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
             float lt = 0.f;
+            if (adds_new) {                                   // weight 2^(score - M), value row v_new
+                const unsigned short* v_row = static_cast<const unsigned short*>(a.v_new) + ((size_t)b * st.Hkv + g) * D + d4;
+                const float wgt = __builtin_amdgcn_exp2f(m_new_tok - M_use);
+                acc = wgt * floatx4{__uint_as_float((unsigned)v_row[0] << 16), __uint_as_float((unsigned)v_row[1] << 16),
+                                    __uint_as_float((unsigned)v_row[2] << 16), __uint_as_float((unsigned)v_row[3] << 16)};
+                lt = wgt;
+            }
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
                 const float wgt = __builtin_amdgcn_exp2f(mw[w] - M_use);

@@ -267,7 +267,8 @@ size_t kvs_workspace_bytes(const kvs_desc* d, int B, int max_q_rows)
 }
 
 static int append_common(const kvs_store* store, int layer, const void* k_new, const void* v_new,
-                         const int32_t* start_pos, int pos_per_head, int B, int T_new, void* stream)
+                         const int32_t* start_pos, int pos_per_head, int B, int T_new, void* stream,
+                         int pos_bias = 0)
 {
     if (int rc = check_store(store, layer)) return rc;
     if (!k_new || !v_new || !start_pos) return fail(KVS_ERR_INVALID_ARG, "k_new, v_new or start_pos is NULL");
@@ -285,6 +286,7 @@ static int append_common(const kvs_store* store, int layer, const void* k_new, c
     a.v = const_cast<void*>(v_new);
     a.start_pos = start_pos;
     a.pos_per_head = pos_per_head;
+    a.pos_bias = pos_bias;
     a.t0 = 0;
     a.B = B;
     a.T = T_new;
@@ -393,6 +395,7 @@ int kvs_gather_kv(const kvs_store* store, int layer, int t0, int T, int B,
     a.v = v_out;
     a.start_pos = nullptr;
     a.pos_per_head = 0;
+    a.pos_bias = 0;
     a.t0 = t0;
     a.B = B;
     a.T = T;
@@ -402,7 +405,8 @@ int kvs_gather_kv(const kvs_store* store, int layer, int t0, int T, int B,
 
 static int attention_common(const kvs_store* store, int layer, const void* q, const int32_t* lens,
                             int lens_per_head, int lens_bias, int B, int T_new, float* out, void* workspace,
-                            size_t workspace_bytes, void* stream)
+                            size_t workspace_bytes, void* stream, const void* k_new = nullptr,
+                            const void* v_new = nullptr)
 {
     if (int rc = check_store(store, layer)) return rc;
     if (!q || !lens || !out) return fail(KVS_ERR_INVALID_ARG, "q, lengths or out is NULL");
@@ -423,6 +427,8 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     a.q = q;
     a.lens = lens;
     a.lens_per_head = lens_per_head;
+    a.k_new = k_new;
+    a.v_new = v_new;
     a.lens_bias = lens_bias;
     a.B = B;
     a.T_new = T_new;
@@ -439,6 +445,22 @@ int kvs_decode_attention(const kvs_store* store, int layer, const void* q, const
                          int B, float* out, void* workspace, size_t workspace_bytes, void* stream)
 {
     return attention_common(store, layer, q, seq_lens, 0, 0, B, 1, out, workspace, workspace_bytes, stream);
+}
+
+int kvs_decode_step(const kvs_store* store, int layer, const void* q, const void* k_new, const void* v_new,
+                    const int32_t* seq_lens, int B, float* out, void* workspace, size_t workspace_bytes,
+                    void* stream)
+{
+    if (int rc = check_store(store, layer)) return rc;
+    if (!k_new || !v_new || !seq_lens) return fail(KVS_ERR_INVALID_ARG, "k_new, v_new or seq_lens is NULL");
+    const bool own = store->host_share_map[layer] == layer;
+    if (own && store->desc.dtype != KVS_BF16) {
+        // other store types: the two launches the fused kernel replaces
+        if (int rc = append_common(store, layer, k_new, v_new, seq_lens, 0, B, 1, stream, -1)) return rc;
+        return attention_common(store, layer, q, seq_lens, 0, 0, B, 1, out, workspace, workspace_bytes, stream);
+    }
+    return attention_common(store, layer, q, seq_lens, 0, 0, B, 1, out, workspace, workspace_bytes, stream,
+                            own ? k_new : nullptr, own ? v_new : nullptr);
 }
 
 int kvs_decode_attention_per_head(const kvs_store* store, int layer, const void* q, const int32_t* kv_lens,

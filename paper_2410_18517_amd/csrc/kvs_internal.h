@@ -19,6 +19,8 @@ struct AttnArgs {
     const void* q;          // device [B][T_new][Hq][D], store dtype
     const int32_t* lens;    // device [B]: decode: tokens in the cache; prefill: position of row 0
     int32_t lens_per_head;  // 1: lens is [B][Hkv], the tokens each kv head of the slot still holds (decode only)
+    const void* k_new;      // decode step that also stores this step's token (bf16 store, own-cache layer):
+    const void* v_new;      //   device [B][1][Hkv][D]; the token sits at position lens[b] - 1.  Else nullptr.
     int32_t lens_bias;      // 0 for decode (row r sees lens + r keys), 1 for prefill
     int32_t B, T_new;
     float* out;             // device fp32 [B][T_new][Hq][D]
@@ -33,6 +35,7 @@ struct CopyArgs {
     void* v;
     const int32_t* start_pos;  // device [B] (append) or nullptr (gather: t0 for all)
     int32_t pos_per_head;      // 1: start_pos is [B][Hkv]
+    int32_t pos_bias;          // added to every start position (-1: the caller passed lengths that count the new row)
     int32_t t0, B, T;
 };
 

@@ -26,7 +26,7 @@ __global__ void copy_rows_kernel(CopyArgs a)
     const int g = (int)((tid / chunks) % st.Hkv);
     const int i = (int)((tid / ((long)chunks * st.Hkv)) % a.T);
     const int b = (int)(tid / ((long)chunks * st.Hkv * a.T));
-    const long pos = (long)(a.start_pos ? a.start_pos[a.pos_per_head ? b * st.Hkv + g : b] : a.t0) + i;
+    const long pos = (long)(a.start_pos ? a.start_pos[a.pos_per_head ? b * st.Hkv + g : b] + a.pos_bias : a.t0) + i;
     if (pos < 0 || pos >= (long)st.max_blocks_per_seq * kPageTokens) return;
     const int slot = resolve_slot(st);
     const int blk = block_of(st, b, (int)(pos / kPageTokens));
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void append_pages_bf16_kernel(CopyArgs a)
     const StoreView& st = a.st;
     const int D = st.head_dim;                    // 64 or 128
     const int g = blockIdx.y, b = blockIdx.z;
-    const long start = a.start_pos[a.pos_per_head ? b * st.Hkv + g : b];
+    const long start = (long)a.start_pos[a.pos_per_head ? b * st.Hkv + g : b] + a.pos_bias;
     const long cap = (long)st.max_blocks_per_seq * kPageTokens;
     if (start < 0 || start >= cap) return;
     const long end = start + a.T < cap ? start + a.T : cap;

@@ -189,6 +189,11 @@ def test_entry_points_reject_bad_arguments_without_touching_the_gpu():
     assert lib.kvs_decode_attention_per_head(C.byref(st), 0, p, None, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_decode_attention_per_head(C.byref(st), 0, None, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_decode_attention_per_head(C.byref(st), 5, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    # the one-launch decode step
+    assert lib.kvs_decode_step(C.byref(st), 0, p, None, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_step(C.byref(st), 0, None, p, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_step(C.byref(st), 4, p, p, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_step(C.byref(st), 0, p, p, p, p, 1, p, None, 0, None) == kb.KVS_ERR_INVALID_ARG
     # distance
     assert lib.kvs_layer_distance(None, 1, 2, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_layer_distance(p, 1, 65, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
