@@ -142,3 +142,30 @@ def test_decode_full_size_fp8_slots(kb):
             want = orc.decode_attention(layer, share, _sub(case, case.K, b), _sub(case, case.V, b),
                                         inputs.to_oracle_array(q[b:b + 1]), lens[b:b + 1])
             assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, (layer, b)
+
+
+@pytest.mark.parametrize("name", ["llama3-8b-32k", "gqa48-ragged"])
+def test_decode_step_full_size_sampled(kb, name):
+    """The one-launch decode step at full size: a donor layer stores its new row and attends, its
+    recipient then attends to the same slot; sampled sequences against the oracle's append + attention."""
+    w = inputs.WORKLOADS[name]
+    share = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)
+    lens = inputs.make_seq_lens(w, 1)
+    recipient = next(l for l in range(w.L) if share[l] != l)
+    donor = int(share[recipient])
+    case = Case(kb, w.L, w.Hq, w.Hkv, w.d, w.B, w.dtype, w.context, share, paged=True, seed=102,
+                fill_layers=[donor], spare_blocks=0)
+    k_new = inputs.normal((w.B, 1, w.Hkv, w.d), 102, 700)
+    v_new = inputs.normal((w.B, 1, w.Hkv, w.d), 102, 701)
+    K, V = list(case.K), list(case.V)
+    K[donor], V[donor] = K[donor].copy(), V[donor].copy()
+    assert orc.append_kv(donor, share, K, V, inputs.to_oracle_array(k_new), inputs.to_oracle_array(v_new), lens - 1)
+    seqs = sorted(set([int(np.argmax(lens)), int(np.argmin(lens))]))
+    for layer in (donor, recipient):
+        q = case.q(layer)
+        got = kb.kvs_decode_step(case.store, layer, q.cuda(), k_new.cuda(), v_new.cuda(), lens).cpu().numpy()
+        for b in seqs:
+            want = orc.decode_attention(layer, share, [None if a is None else a[b:b + 1] for a in K],
+                                        [None if a is None else a[b:b + 1] for a in V],
+                                        inputs.to_oracle_array(q[b:b + 1]), lens[b:b + 1])
+            assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, (layer, b)
