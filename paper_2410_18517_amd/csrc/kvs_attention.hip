@@ -732,6 +732,9 @@ void attn_bf16_wide_kernel(AttnArgs a)
     constexpr int kDepth = NT == 1 ? 2 : 4;                        // fewer registers where occupancy matters more
     constexpr int kPasses = (kPageVecs + kWideThreads - 1) / kWideThreads;   // passes of the workgroup over one page
     u32x4 stage[kDepth][2 * kPasses];
+    // With one column block per (sequence, kv head) every page is read exactly once per launch and
+    // is streamed past the caches; with several, the later blocks find it in L2.
+    const bool read_once = gridDim.z == 1;
     // Each page of the pair is copied by whole passes of the workgroup, so that the page index --
     // and with it the page-table entry -- is the same for every thread of a pass: a scalar load,
     // which does not queue behind the vector loads already in flight.
@@ -742,7 +745,8 @@ void attn_bf16_wide_kernel(AttnArgs a)
         const u32x4* src = reinterpret_cast<const u32x4*>(pool + page_offset(st, slot, safe_block_of(st, b, page), g)); \
         _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                         \
             const int v = i * kWideThreads + (int)threadIdx.x;                                        \
-            if (kPageVecs % kWideThreads == 0 || v < kPageVecs) stage[slot_][pg * kPasses + i] = src[v]; \
+            if (kPageVecs % kWideThreads == 0 || v < kPageVecs)                                       \
+                stage[slot_][pg * kPasses + i] = read_once ? __builtin_nontemporal_load(src + v) : src[v]; \
         }                                                                                             \
     }
 #define KVS_PUT_PAIR(buf, slot_)                                                                      \

@@ -76,3 +76,34 @@ def test_store_holds_only_unshared_layers(kb):
     shared = kb.KVStore(share, w.Hq, w.Hkv, w.d, "bf16", 64, 8)
     assert shared.desc.n_slots == 28 and full.desc.n_slots == 40          # the main table's "Layer" column
     assert shared.pool.numel() * 40 == full.pool.numel() * 28
+
+
+def test_corrupt_page_table_entries_stay_inside_the_pool(kb):
+    """Page-table entries outside [0, num_blocks) for one sequence: appends to them are dropped,
+    reads are forced into the pool; the other sequence is served correctly and nothing faults."""
+    from helpers import rel_l2_rows, REL_L2_ATTENTION
+    L, Hq, Hkv, d, B, cap = 2, 4, 2, 128, 2, 64
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, "bf16", cap, share, paged=True, seed=13, fill_tokens=cap)
+    bad = case.block_table.copy()
+    bad[1] = [-3, 10 ** 9, case.num_blocks, -(2 ** 31)]
+    store = kb.KVStore(share, Hq, Hkv, d, "bf16", case.num_blocks, case.max_blocks, block_table=bad)
+    store.pool.copy_(case.store.pool)                                  # same contents, corrupt table for sequence 1
+    lens = np.array([cap, cap], np.int32)
+    q = case.q(1)
+    k_new = inputs.normal((B, 3, Hkv, d), 13, 900)
+    assert kb.kvs_append_kv(store, 0, k_new.cuda(), k_new.cuda(), np.array([5, 5], np.int32)) == kb.KVS_OK
+    K, V = [case.K[0].copy(), None], [case.V[0].copy(), None]
+    K[0][0, 5:8] = V[0][0, 5:8] = inputs.to_oracle_array(k_new)[0]
+    for call in (lambda: kb.kvs_decode_attention(store, 1, q.cuda(), lens),
+                 lambda: kb.kvs_decode_step(store, 0, q.cuda(), k_new[:, :1].contiguous().cuda(), k_new[:, :1].contiguous().cuda(), lens)):
+        got = call().cpu().numpy()
+        assert np.isfinite(got[0]).all()
+    K[0][0, cap - 1] = V[0][0, cap - 1] = inputs.to_oracle_array(k_new)[0, 0]     # the step's own row
+    want = orc.decode_attention(1, share, [K[0][:1], None], [V[0][:1], None], inputs.to_oracle_array(q[:1]), lens[:1])
+    got = kb.kvs_decode_attention(store, 1, q.cuda(), lens).cpu().numpy()
+    assert rel_l2_rows(got[:1], want).max() <= REL_L2_ATTENTION
+    pre = kb.kvs_prefill_attention(store, 1, case.q(1, rows=20).cuda(), np.array([10, 10], np.int32)).cpu().numpy()
+    assert np.isfinite(pre[0]).all()
+    k, v = kb.kvs_gather_kv(store, 1, 0, cap, B)
+    assert np.array_equal(inputs.to_oracle_array(k)[0], K[0][0])
