@@ -24,6 +24,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 // ------------------------------------------------------------------ fp32 store
 // One wavefront per (sequence, query row, query head); the whole context in one pass.
@@ -341,6 +342,32 @@ __device__ __forceinline__ void pair_values(u32x4 (&va)[D / 32], u32x4 (&vb)[D /
             o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vcat), pf[ct],
                                                                o[ct][c], 0, 0, 0);
     }
+}
+
+// The same for value operands that already arrive as the eight-token operands of a pair (the
+// shared-page kernels lay them out that way in LDS): words x, y of vcat[c] are the first page's
+// four tokens of channel tile c, words z, w the second page's.
+template <int D, int NT>
+__device__ __forceinline__ void pair_values_cat(u32x4 (&vcat)[D / 16], bool have_b, int tok_a, int tok_b, int n_max,
+                                                int quad, const bf16x8 (&pf)[NT], floatx4 (&o)[NT][D / 16])
+{
+    constexpr int DT = D / 16;
+    if (!have_b || tok_b + kPageTokens > n_max) {            // some token of the pair lies past the stored length
+        const int fa = n_max - tok_a - quad * 4, fb = have_b ? n_max - tok_b - quad * 4 : 0;
+        const unsigned a01 = (0 < fa ? 0x0000ffffu : 0u) | (1 < fa ? 0xffff0000u : 0u);
+        const unsigned a23 = (2 < fa ? 0x0000ffffu : 0u) | (3 < fa ? 0xffff0000u : 0u);
+        const unsigned b01 = (0 < fb ? 0x0000ffffu : 0u) | (1 < fb ? 0xffff0000u : 0u);
+        const unsigned b23 = (2 < fb ? 0x0000ffffu : 0u) | (3 < fb ? 0xffff0000u : 0u);
+#pragma unroll
+        for (int c = 0; c < DT; ++c) {
+            vcat[c].x &= a01; vcat[c].y &= a23; vcat[c].z &= b01; vcat[c].w &= b23;
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < DT; ++c)
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct)
+            o[ct][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vcat[c]), pf[ct], o[ct][c], 0, 0, 0);
 }
 
 template <int D, int NT>
@@ -662,9 +689,10 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 // prefix again: 64 flops per byte, which the memory system, not the matrix cores, then bounds.
 // Here the wavefronts of a workgroup each take their own columns (256 per workgroup as 8 x 32, or
 // 64 as 4 x 16 when a head has fewer) and all consume the same page pair: the pair is fetched once per workgroup (each thread a few 16-byte pieces, one
-// pair ahead, in registers), laid into LDS as the plain image of the two pages -- the in-page
-// order is the operand order, so a lane's operand is the 16 bytes at its own index -- and read
-// back by each wavefront after a barrier.  A wavefront owns its columns for the whole context:
+// pair ahead, in registers) and laid into LDS in operand order: keys as the plain image of the
+// two pages (the in-page order is the operand order, so a lane's operand is the 16 bytes at its
+// own index), values with the two pages' halves interleaved, so that a lane reads the eight-token
+// operand of the value product in one piece; each wavefront reads them back after a barrier.  A wavefront owns its columns for the whole context:
 // no state is merged, no splits, the output is written normalised.  Causality: a wavefront
 // skips the pairs that lie beyond the last key any of its columns sees.
 // NT 16-column tiles per wavefront, WAVES wavefronts: NT * 16 * WAVES columns per workgroup.
@@ -674,6 +702,10 @@ void attn_bf16_wide_kernel(AttnArgs a)
 {
     constexpr int KS = D / 32, DT = D / 16;
     constexpr int kWideThreads = WAVES * 64, kWideCols = WAVES * NT * 16;
+    // The large variant lays the values into LDS as the eight-token operands of a page pair (no
+    // register shuffling before the value product); the small one, tight on registers at three
+    // wavefronts per SIMD, keeps the plain page image and concatenates in registers.
+    constexpr bool kCatV = NT > 1;
     constexpr int kPageVecs = kPageTokens * D * 2 * 2 / 16;        // 16-byte pieces of one page (K then V)
     const StoreView& st = a.st;
     const int lane = threadIdx.x & 63;
@@ -753,8 +785,19 @@ void attn_bf16_wide_kernel(AttnArgs a)
     _Pragma("unroll") for (int pg = 0; pg < 2; ++pg)                                                  \
         _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                         \
             const int v = i * kWideThreads + (int)threadIdx.x;                                        \
-            if (kPageVecs % kWideThreads == 0 || v < kPageVecs)                                       \
-                tile[buf][pg * kPageVecs + v] = stage[slot_][pg * kPasses + i];                       \
+            if (kPageVecs % kWideThreads == 0 || v < kPageVecs) {                                     \
+                const u32x4 piece = stage[slot_][pg * kPasses + i];                                   \
+                if (!kCatV) {                                    /* the page as it is */              \
+                    tile[buf][pg * kPageVecs + v] = piece;                                            \
+                } else if (v < KS * 64) {                        /* a key piece: the page's own order */ \
+                    tile[buf][pg * KS * 64 + v] = piece;                                              \
+                } else {                                         /* a value piece: halves to two pair operands */ \
+                    const int vs = (v - KS * 64) >> 6, vl = v & 63;                                   \
+                    u32x2* dst = reinterpret_cast<u32x2*>(&tile[buf][2 * KS * 64 + (2 * vs) * 64 + vl]) + pg; \
+                    dst[0] = u32x2{piece.x, piece.y};                                                 \
+                    dst[2 * 64] = u32x2{piece.z, piece.w};                                            \
+                }                                                                                     \
+            }                                                                                         \
         }
 
     const float scale_log2 = 1.44269504088896340736f * (D == 128 ? 0.08838834764831845f : 0.125f);
@@ -787,22 +830,33 @@ void attn_bf16_wide_kernel(AttnArgs a)
                     const bool have_b = 2 * pair + 1 < my_pages;
                     // keys first; the value operands are fetched from LDS once the score products are
                     // issued, into the registers the keys no longer need
-                    u32x4 ka[KS], kb[KS], va[KS], vb[KS];
+                    constexpr int kSecond = kCatV ? KS * 64 : kPageVecs;   // where the second page's keys start
+                    u32x4 ka[KS], kb[KS];
 #pragma unroll
                     for (int s = 0; s < KS; ++s) {
                         ka[s] = tile[buf][s * 64 + lane];
-                        kb[s] = tile[buf][kPageVecs + s * 64 + lane];       // an absent second page is zeroed below
+                        kb[s] = tile[buf][kSecond + s * 64 + lane];        // an absent second page is zeroed below
                     }
                     floatx4 sa[NT], sb[NT];
                     bf16x8 pf[NT];
                     pair_qk<D, NT>(ka, kb, have_b, qf, sa, sb);
+                    // the value operands travel under the softmax, into the registers the keys no longer need
+                    if constexpr (kCatV) {
+                        u32x4 vcat[DT];
 #pragma unroll
-                    for (int s = 0; s < KS; ++s) {                         // travel under the softmax arithmetic
-                        va[s] = tile[buf][(KS + s) * 64 + lane];
-                        vb[s] = tile[buf][kPageVecs + (KS + s) * 64 + lane];
+                        for (int c = 0; c < DT; ++c) vcat[c] = tile[buf][2 * KS * 64 + c * 64 + lane];
+                        pair_softmax<D, NT>(sa, sb, have_b, tok_a, tok_b, n_min, n_col, m, l, o, quad, scale_log2, pf);
+                        pair_values_cat<D, NT>(vcat, have_b, tok_a, tok_b, n_max, quad, pf, o);
+                    } else {
+                        u32x4 va[KS], vb[KS];
+#pragma unroll
+                        for (int s = 0; s < KS; ++s) {
+                            va[s] = tile[buf][(KS + s) * 64 + lane];
+                            vb[s] = tile[buf][kPageVecs + (KS + s) * 64 + lane];
+                        }
+                        pair_softmax<D, NT>(sa, sb, have_b, tok_a, tok_b, n_min, n_col, m, l, o, quad, scale_log2, pf);
+                        pair_values<D, NT>(va, vb, have_b, tok_a, tok_b, n_max, quad, pf, o);
                     }
-                    pair_softmax<D, NT>(sa, sb, have_b, tok_a, tok_b, n_min, n_col, m, l, o, quad, scale_log2, pf);
-                    pair_values<D, NT>(va, vb, have_b, tok_a, tok_b, n_max, quad, pf, o);
                 }
                 if (pair + 1 < wg_pairs) {
                     KVS_PUT_PAIR(buf ^ 1, (j + 1) % kDepth)            // that buffer was last read before the previous barrier
