@@ -17,11 +17,11 @@
 //
 // A prefill chunk (more than 32 rows) is a matrix product bounded by the matrix cores and takes
 // the tiled kernel instead: a workgroup of eight wavefronts owns 256 rows and one whole head of
-// K or V, stages 256 x 64 pieces of x and 128 x 64 pieces of the head's weight rows through
-// double-buffered LDS (the 16-byte pieces of a row are XOR-swizzled by the row index, so that the
-// operand reads of a wavefront fall on distinct banks without padding), and each wavefront keeps
-// a 64 x (head_dim/2) block of accumulators whose columns again hold both ends of the rotary
-// pairs.  Global loads run two steps ahead of their use, operand reads half a step ahead.
+// K or V; the 256 x 64 pieces of x and 128 x 64 pieces of the head's weight rows go from global
+// memory straight into LDS (global_load_lds_dwordx4), three buffers deep, with the 16-byte pieces
+// of a row XOR-swizzled by the row index so that the operand reads of a wavefront fall on
+// distinct banks without padding; each wavefront keeps a 64 x (head_dim/2) block of accumulators
+// whose columns again hold both ends of the rotary pairs.
 #include <hip/hip_runtime.h>
 
 #include "kvs_internal.h"
@@ -218,8 +218,8 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
     const int M = a.B * a.T;
     const int m0 = blockIdx.y * kTileRows;
 
-    __shared__ __attribute__((aligned(16))) unsigned short sa[2][kTileRows][kLdsRow];
-    __shared__ __attribute__((aligned(16))) unsigned short sb[2][D][kLdsRow];
+    __shared__ __attribute__((aligned(16))) unsigned short sa[3][kTileRows][kLdsRow];
+    __shared__ __attribute__((aligned(16))) unsigned short sb[3][D][kLdsRow];
 
     const unsigned short* x = static_cast<const unsigned short*>(a.x);
     const unsigned short* w = static_cast<const unsigned short*>(is_v ? a.w_v : a.w_k) + (size_t)head * D * a.hidden;
@@ -254,10 +254,16 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
         row_pos[threadIdx.x] = off < 0 ? 0 : (int)pos;
     }
 
-    // staging: piece id = thread + 512 j  ->  row id/8, 16-byte column id%8 (8 threads cover a row's 128 bytes).
-    // Rows past the last one re-read the last row; their accumulators are never stored.
-    const int s_col = (threadIdx.x & 7) * 8;
+    // Staging goes from global memory straight into LDS (global_load_lds_dwordx4: lane L of a
+    // wavefront fetches 16 bytes from its own address and the hardware writes them at the
+    // wavefront's LDS base + 16 L), so the tiles in flight occupy no registers and no LDS store
+    // instructions are issued.  LDS piece p = 512 j + thread of a tile is piece p % 8 of row p / 8;
+    // the swizzle (piece q of row r sits at q ^ (r & 7)) is applied on the global side: the lane
+    // fetches the piece that belongs where it writes.  Rows past the last one re-read the last row;
+    // their accumulators are never stored.
     const int s_row = threadIdx.x >> 3;                            // + 64 j
+    const int s_col = ((threadIdx.x & 7) ^ (s_row & 7)) * 8;       // 64 j keeps row & 7
+    const int wave_row = __builtin_amdgcn_readfirstlane(wave * 8); // first LDS row the wavefront writes in a pass
     const unsigned short* src_a[kAChunks];
     const unsigned short* src_b[kBChunks];
 #pragma unroll
@@ -267,7 +273,6 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
     }
 #pragma unroll
     for (int j = 0; j < kBChunks; ++j) src_b[j] = w + (size_t)(s_row + kStageRows * j) * a.hidden + k_begin + s_col;
-    uintx4 ra[2][kAChunks], rb[2][kBChunks];                       // two steps of the tiles in flight
 
     floatx4 acc[4][NT];
 #pragma unroll
@@ -275,16 +280,17 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
 #pragma unroll
         for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-#define KVS_FETCH(step, set)                                                                         \
+    // The load is written as assembly: seen as an LDS write by the compiler, every LDS read after it
+    // would be made to wait for it (the two cannot be told apart by address), which would undo the
+    // prefetch; the waits that matter are spelled out at the barrier instead.
+#define KVS_LOAD_TO_LDS(gptr, lds_ptr)                                                               \
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"                    \
+                 :: "v"(gptr), "s"((unsigned)(size_t)(lds_ptr)) : "memory")
+#define KVS_FETCH(step, buf)                                                                         \
     _Pragma("unroll") for (int j = 0; j < kAChunks; ++j)                                             \
-        ra[set][j] = *reinterpret_cast<const uintx4*>(src_a[j] + (step) * kTileK);                   \
+        KVS_LOAD_TO_LDS(src_a[j] + (step) * kTileK, &sa[buf][wave_row + kStageRows * j][0]);         \
     _Pragma("unroll") for (int j = 0; j < kBChunks; ++j)                                             \
-        rb[set][j] = *reinterpret_cast<const uintx4*>(src_b[j] + (step) * kTileK);
-#define KVS_STAGE(buf, set)                                                                          \
-    _Pragma("unroll") for (int j = 0; j < kAChunks; ++j)                                             \
-        *reinterpret_cast<uintx4*>(&sa[buf][s_row + kStageRows * j][s_col ^ ((s_row & 7) * 8)]) = ra[set][j]; \
-    _Pragma("unroll") for (int j = 0; j < kBChunks; ++j)                                             \
-        *reinterpret_cast<uintx4*>(&sb[buf][s_row + kStageRows * j][s_col ^ ((s_row & 7) * 8)]) = rb[set][j];
+        KVS_LOAD_TO_LDS(src_b[j] + (step) * kTileK, &sb[buf][wave_row + kStageRows * j][0]);
 #define KVS_READ(buf, kk, fa, fb)                                                                    \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
         fa[i] = *reinterpret_cast<const bf16x8*>(&sa[buf][wm * 64 + i * 16 + l16][((kk) + quad * 8) ^ ((l16 & 7) * 8)]); \
@@ -308,45 +314,56 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
     }
 
     // A step is two half-steps of 32 along the contraction, and the workgroup's barrier sits
-    // between them, not at the step's end.  Step s
-    //   - starts the global loads of the tiles of step s+2,
+    // between them, not at the step's end.  Three LDS buffers rotate.  Step s
+    //   - starts the loads of the tiles of step s+2 into buffer (s+2)%3, whose last readers waited
+    //     for their data before the barrier of step s-1,
     //   - multiplies its first half (operands already in registers) while it reads its second
-    //     half's operands from LDS buffer s%2,
-    //   - writes the tiles of step s+1 (loaded during step s-1) to the other buffer; barrier;
+    //     half's operands from buffer s%3,
+    //   - waits until its own loads of step s+1 (issued a step ago) have landed; barrier;
     //   - multiplies its second half while it reads the first half's operands of step s+1.
-    // Every LDS read therefore has sixteen matrix instructions to hide behind, and nobody still
-    // reads the buffer being written: its last readers waited for their data before the barrier
-    // of the step before.  The number of steps is even; the last two steps re-load and re-stage
-    // the last tiles, which nobody uses, so that every step is the same straight-line code.
-#define KVS_STEP(step, set)                                                                          \
+    // Every LDS read has sixteen matrix instructions to hide behind and every global load two
+    // steps.  The last two steps re-load the last tiles into a free buffer, which nobody reads, so
+    // that every step is the same straight-line code.  The barrier is the bare instruction with the
+    // waits spelled out: a fence would also wait for the loads that were only just issued.
+    constexpr int kLoads = kAChunks + kBChunks;                    // global loads a thread issues per step
+    // vmcnt(kLoads): all but this step's loads have landed; lgkmcnt(0): this wavefront's LDS reads are done
+#define KVS_WAIT_OLDER asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(kLoads) : "memory")
+#define KVS_STEP(step, b0, b1, b2)                                                                   \
     {                                                                                                \
         const int ahead = (step) + 2 < n_steps ? (step) + 2 : n_steps - 1;                           \
-        KVS_FETCH(ahead, set)                                                                        \
-        KVS_READ(set, 32, fa1, fb1)                                                                  \
+        KVS_FETCH(ahead, b2)                                                                         \
+        KVS_READ(b0, 32, fa1, fb1)                                                                   \
         KVS_MULTIPLY(fa0, fb0)                                                                       \
-        KVS_STAGE(set ^ 1, set ^ 1)                                                                  \
-        if constexpr (NT == 4) __builtin_amdgcn_sched_group_barrier(0x020, kAChunks + kBChunks, 0);  \
+        if constexpr (NT == 4) __builtin_amdgcn_sched_group_barrier(0x020, kLoads, 0);               \
         KVS_FOURS_WITH_READS                                                                         \
-        __syncthreads();                                                                             \
-        KVS_READ(set ^ 1, 0, fa0, fb0)                                                               \
+        KVS_WAIT_OLDER;                                                                              \
+        __builtin_amdgcn_s_barrier();                                                                \
+        KVS_READ(b1, 0, fa0, fb0)                                                                    \
         KVS_MULTIPLY(fa1, fb1)                                                                       \
         KVS_FOURS_WITH_READS                                                                         \
     }
     bf16x8 fa0[4], fb0[NT], fa1[4], fb1[NT];
     KVS_FETCH(0, 0)
-    KVS_STAGE(0, 0)
     KVS_FETCH(1, 1)
-    __syncthreads();
+    KVS_WAIT_OLDER;                                                // the tiles of step 0 have landed
+    __builtin_amdgcn_s_barrier();
     KVS_READ(0, 0, fa0, fb0)
-    for (int step = 0; step < n_steps; step += 2) {
-        KVS_STEP(step, 0)
-        KVS_STEP(step + 1, 1)
+    int b0 = 0, b1 = 1, b2 = 2;
+    for (int step = 0; step < n_steps; ++step) {
+        KVS_STEP(step, b0, b1, b2)
+        const int t = b0;
+        b0 = b1;
+        b1 = b2;
+        b2 = t;
     }
+    // the last steps' spare loads must have landed before this workgroup's LDS can be handed on
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #undef KVS_STEP
+#undef KVS_WAIT_OLDER
 #undef KVS_FOURS_WITH_READS
 #undef KVS_READ
 #undef KVS_FETCH
-#undef KVS_STAGE
+#undef KVS_LOAD_TO_LDS
 #undef KVS_MULTIPLY
 
     // lane holds, of tile (i, j), column l16 and rows 4*quad .. 4*quad+3
