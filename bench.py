@@ -297,6 +297,8 @@ def main():
     ap.add_argument("--split-tokens", type=int, default=0)
     ap.add_argument("--two-calls", action="store_true",
                     help="decode mode: kvs_append_kv + kvs_decode_attention per layer instead of kvs_decode_step")
+    ap.add_argument("--graph", action="store_true",
+                    help="decode mode: record the step's launches once into a HIP graph and time its replays")
     ap.add_argument("--store", choices=["fp8"], default=None,
                     help="decode mode: keep the slots in fp8 (E4M3) instead of the workload's type")
     ap.add_argument("--prefill-rows", type=int, default=0,
@@ -389,6 +391,15 @@ def main():
         del src, dst
 
     print("store filled, timing", file=sys.stderr, flush=True)
+    if args.graph:
+        # kernel nodes only (the library records no memsets and allocates nothing); the lengths are
+        # a device array, so a serving loop would advance them between replays
+        step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        step = graph.replay
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -431,7 +442,8 @@ def main():
                    "batch": w.B, "context": w.context if w.min_context is None else [w.min_context, w.context],
                    "page_tokens": 16, "shared_layers": w.n_shared, "kv_slots": int(store.desc.n_slots),
                    "step": "kvs_append_kv + kvs_decode_attention per layer" if args.two_calls
-                           else "kvs_decode_step per layer"},
+                           else "kvs_decode_step per layer",
+                   "launch": "HIP graph replay" if args.graph else "eager"},
         "hbm_gbps": round(alg_bytes * w.L / (ms_per_step * 1e-3) / 1e9, 1),
         "hbm_frac": round(alg_bytes * w.L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "roofline": roofline,
