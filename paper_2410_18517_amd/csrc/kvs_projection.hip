@@ -446,6 +446,198 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
         }
 }
 
+// ---- tiled kernel for very many rows: two heads per workgroup -------------------------------
+//
+// With 256 x 128 output tiles the x and weight tiles that cross from L2 into the compute units
+// (3.1 GB for 8192 rows at hidden 4096, 16 heads) take longer than the arithmetic.  This variant
+// gives a workgroup 256 rows and two adjacent head blocks of the list [K heads, V heads]: a third
+// fewer bytes per flop, three operand reads per eight matrix instructions instead of four, and
+// one barrier per 64 matrix instructions of a wavefront instead of 32.  A wavefront owns
+// 128 rows x (32 + 32) channels, the two ends of the rotary pairs of one head block.  Two LDS
+// buffers of 64 KiB; a step runs in four quarters of sixteen matrix instructions (contraction
+// half x row half), every quarter reading the operands of the next one:
+//   q0  rows 0-63,  k 0-31    | reads x rows 64-127, k 0-31
+//   q1  rows 64-127, k 0-31   | reads weights k 32-63 and x rows 0-63, k 32-63
+//   q2  rows 0-63,  k 32-63   | reads x rows 64-127, k 32-63; then waits for the next step's tiles, barrier
+//   q3  rows 64-127, k 32-63  | starts the loads of step + 2 into the buffer just freed; reads the
+//                             | first operands of step + 1 from the other buffer
+// head_dim 128 only, no contraction split (it is chosen when the tiles alone fill the chip).
+constexpr int kPairCols = 256;
+
+__global__ __launch_bounds__(kTiledThreads) void project_append_pair_kernel(ProjectArgs a)
+{
+    constexpr int D = 128, half = D / 2;
+    constexpr int kChunks = kTileRows * (kTileK / 8) / kTiledThreads;   // 16-byte pieces per thread of either tile: 4
+    const StoreView& st = a.st;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int quad = lane >> 4, l16 = lane & 15;
+    const int wm = wave >> 2, wn = wave & 3;
+    // Workgroups go to the eight XCDs round-robin by their linear index, and each XCD has its own
+    // L2.  Index i is therefore read as (XCD i % 8, place i / 8 in it), and an XCD is given whole
+    // row tiles with all their head pairs: the x rows are then fetched into one L2 once and hit
+    // there by the other pairs' workgroups, which run at the same time.
+    const int n_pairs = st.Hkv;
+    const int place = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+    const int pair = place % n_pairs;
+    const int row_tile = (place / n_pairs) * 8 + xcd;
+    const int M = a.B * a.T;
+    if (row_tile * kTileRows >= M) return;                         // padding of the last group of eight row tiles
+    const int hb = pair * 2 + (wn >> 1);                           // this wavefront's head block
+    const int strip = wn & 1;
+    const int is_v = hb >= st.Hkv;
+    const int head = is_v ? hb - st.Hkv : hb;
+    const int m0 = row_tile * kTileRows;
+
+    __shared__ __attribute__((aligned(16))) unsigned short sa[2][kTileRows][kLdsRow];
+    __shared__ __attribute__((aligned(16))) unsigned short sb[2][kPairCols][kLdsRow];
+    __shared__ long long row_block[kTileRows];                     // slot * num_blocks + block of the row's page, -1: dropped
+    __shared__ int row_pos[kTileRows];
+
+    const unsigned short* x = static_cast<const unsigned short*>(a.x);
+    const int n_steps = a.hidden / kTileK;                         // even: hidden is a multiple of 128
+
+    if (threadIdx.x < kTileRows) {
+        const int m = m0 + threadIdx.x;
+        long long blk_of_row = -1;
+        long pos = 0;
+        if (m < M) {
+            const int b = m / a.T;
+            pos = (long)a.start_pos[b] + m % a.T;
+            if (pos >= 0 && pos < (long)st.max_blocks_per_seq * kPageTokens) {
+                int donor = st.share_map[st.layer];
+                donor = donor < 0 ? 0 : (donor >= st.L ? st.L - 1 : donor);
+                int slot = st.slot_of_layer[donor];
+                slot = slot < 0 ? 0 : (slot >= st.n_slots ? st.n_slots - 1 : slot);
+                const size_t bidx = (size_t)b * st.max_blocks_per_seq + (size_t)(pos / kPageTokens);
+                const int blk = st.block_table ? st.block_table[bidx] : (int)bidx;
+                if (blk >= 0 && blk < st.num_blocks) blk_of_row = (long long)slot * st.num_blocks + blk;
+            }
+        }
+        row_block[threadIdx.x] = blk_of_row;
+        row_pos[threadIdx.x] = blk_of_row < 0 ? 0 : (int)pos;
+    }
+
+    // staging as in the kernel above: piece p = 512 j + thread is piece p % 8 of row p / 8, swizzled
+    // on the global side; weight rows 0-127 of the tile are the first head block, 128-255 the second
+    const int s_row = threadIdx.x >> 3;
+    const int s_col = ((threadIdx.x & 7) ^ (s_row & 7)) * 8;
+    const int wave_row = __builtin_amdgcn_readfirstlane(wave * 8);
+    const unsigned short* src_a[kChunks];
+    const unsigned short* src_b[kChunks];
+#pragma unroll
+    for (int j = 0; j < kChunks; ++j) {
+        const int m = m0 + s_row + kStageRows * j;
+        src_a[j] = x + (size_t)(m < M ? m : M - 1) * a.hidden + s_col;
+        const int blk = pair * 2 + j / 2;                          // rows 64 j .. 64 j + 63 of the weight tile
+        const unsigned short* wbase = blk >= st.Hkv ? static_cast<const unsigned short*>(a.w_v) + (size_t)(blk - st.Hkv) * D * a.hidden
+                                                    : static_cast<const unsigned short*>(a.w_k) + (size_t)blk * D * a.hidden;
+        src_b[j] = wbase + (size_t)(s_row + kStageRows * (j % 2)) * a.hidden + s_col;
+    }
+
+    floatx4 acc[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+#define KVS_LOAD_TO_LDS(gptr, lds_ptr)                                                               \
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"                    \
+                 :: "v"(gptr), "s"((unsigned)(size_t)(lds_ptr)) : "memory")
+#define KVS_FETCH(step, buf)                                                                         \
+    _Pragma("unroll") for (int j = 0; j < kChunks; ++j)                                              \
+        KVS_LOAD_TO_LDS(src_a[j] + (step) * kTileK, &sa[buf][wave_row + kStageRows * j][0]);         \
+    _Pragma("unroll") for (int j = 0; j < kChunks; ++j)                                              \
+        KVS_LOAD_TO_LDS(src_b[j] + (step) * kTileK, &sb[buf][wave_row + kStageRows * j][0]);
+#define KVS_READ_A(buf, kk, rh, fa)                                                                  \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
+        fa[i] = *reinterpret_cast<const bf16x8*>(&sa[buf][wm * 128 + (rh) * 64 + i * 16 + l16][((kk) + quad * 8) ^ ((l16 & 7) * 8)]);
+#define KVS_READ_B(buf, kk, fb)                                                                      \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                  \
+        const int col = (wn >> 1) * D + (j < 2 ? 0 : half) + strip * 32 + (j % 2) * 16 + l16;        \
+        fb[j] = *reinterpret_cast<const bf16x8*>(&sb[buf][col][((kk) + quad * 8) ^ ((l16 & 7) * 8)]); \
+    }
+#define KVS_MULTIPLY(rh, fa, fb)                                                                     \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
+            acc[(rh) * 4 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[(rh) * 4 + i][j], 0, 0, 0);
+#define KVS_SPREAD_READS(per_four)                                                                   \
+    _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                  \
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);                                           \
+        __builtin_amdgcn_sched_group_barrier(0x100, per_four, 0);                                    \
+    }
+    // all of this wavefront's loads have landed and its LDS reads are done
+#define KVS_WAIT_ALL asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory")
+#define KVS_STEP(step, buf)                                                                          \
+    {                                                                                                \
+        KVS_READ_A(buf, 0, 1, fa1)                                                                   \
+        KVS_MULTIPLY(0, fa0, fb0)                                                                    \
+        KVS_SPREAD_READS(1)                                                                          \
+        KVS_READ_B(buf, 32, fb1)                                                                     \
+        KVS_READ_A(buf, 32, 0, fa0)                                                                  \
+        KVS_MULTIPLY(1, fa1, fb0)                                                                    \
+        KVS_SPREAD_READS(2)                                                                          \
+        KVS_READ_A(buf, 32, 1, fa1)                                                                  \
+        KVS_MULTIPLY(0, fa0, fb1)                                                                    \
+        KVS_SPREAD_READS(1)                                                                          \
+        KVS_WAIT_ALL;                                                                                \
+        __builtin_amdgcn_s_barrier();                                                                \
+        if ((step) + 2 < n_steps) { KVS_FETCH((step) + 2, buf) }                                     \
+        KVS_READ_B(1 - (buf), 0, fb0)                                                                \
+        KVS_READ_A(1 - (buf), 0, 0, fa0)                                                             \
+        KVS_MULTIPLY(1, fa1, fb1)                                                                    \
+        KVS_SPREAD_READS(2)                                                                          \
+    }
+    bf16x8 fa0[4], fa1[4], fb0[4], fb1[4];
+    KVS_FETCH(0, 0)
+    KVS_WAIT_ALL;
+    __builtin_amdgcn_s_barrier();
+    KVS_FETCH(1, 1)
+    KVS_READ_B(0, 0, fb0)
+    KVS_READ_A(0, 0, 0, fa0)
+    for (int step = 0; step < n_steps; step += 2) {
+        KVS_STEP(step, 0)
+        KVS_STEP(step + 1, 1)
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef KVS_STEP
+#undef KVS_WAIT_ALL
+#undef KVS_SPREAD_READS
+#undef KVS_MULTIPLY
+#undef KVS_READ_B
+#undef KVS_READ_A
+#undef KVS_FETCH
+#undef KVS_LOAD_TO_LDS
+
+    // lane holds, of tile (i, j), column l16 and rows 4*quad .. 4*quad+3
+    const bool rotate = !is_v && a.rope_cos;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = wm * 128 + i * 16 + quad * 4 + r;
+            const long long rb = row_block[row];
+            const int pos = row_pos[row];
+            unsigned short* page = static_cast<unsigned short*>(st.pool) +
+                                   (((size_t)(rb < 0 ? 0 : rb) * st.Hkv + head) * 2 + is_v) * (size_t)(kPageTokens * D);
+            const int t = pos % kPageTokens;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int c = strip * 32 + j * 16 + l16;
+                float lo = acc[i][j][r], hi = acc[i][j + 2][r];
+                if (rotate) {                                      // dropped rows read table row 0
+                    const float cs = a.rope_cos[(size_t)pos * half + c], sn = a.rope_sin[(size_t)pos * half + c];
+                    const float rl = lo * cs - hi * sn, rh = hi * cs + lo * sn;
+                    lo = rl;
+                    hi = rh;
+                }
+                if (rb >= 0) {
+                    page[is_v ? v_index(t, c) : k_index(t, c)] = round_bf16(lo);
+                    page[is_v ? v_index(t, c + half) : k_index(t, c + half)] = round_bf16(hi);
+                }
+            }
+        }
+}
+
 }  // namespace
 
 // Which kernel a call takes and how far its contraction is split across workgroups.
@@ -453,8 +645,11 @@ namespace {
 constexpr long kTargetWorkgroups = 256;                  // one per compute unit measured fastest
 constexpr int kTiledFromRows = 33;                       // more rows than this: the tiled kernel
 
+constexpr long kPairFromTiles = 192;                     // two-head tiles that fill the chip by themselves
+
 struct ProjectPlan {
     bool tiled;
+    bool pair;                   // two head blocks per workgroup
     int k_splits;
     size_t tiles;                // output tiles = arrival counters
     size_t partial_bytes;        // per tile and split
@@ -464,6 +659,13 @@ ProjectPlan plan_project(int Hkv, int head_dim, int hidden, int rows)
 {
     ProjectPlan p;
     p.tiled = rows >= kTiledFromRows;
+    p.pair = p.tiled && head_dim == 128 && (long)Hkv * ((rows + kTileRows - 1) / kTileRows) >= kPairFromTiles;
+    if (p.pair) {
+        p.tiles = (size_t)Hkv * ((rows + kTileRows - 1) / kTileRows);
+        p.partial_bytes = 0;
+        p.k_splits = 1;
+        return p;
+    }
     long most;                   // splits that leave every workgroup enough contraction
     int unit;                    // the contraction of one split is a multiple of this
     if (p.tiled) {
@@ -502,7 +704,11 @@ int launch_project_append(ProjectArgs a, void* workspace, void* stream)
     a.counters = static_cast<int32_t*>(workspace);
     a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(p.tiles));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (p.tiled) {
+    if (p.pair) {
+        const unsigned row_tiles = (unsigned)((rows + kTileRows - 1) / kTileRows);
+        const dim3 grid((row_tiles + 7) / 8 * 8 * a.st.Hkv, 1, 1);
+        hipLaunchKernelGGL(project_append_pair_kernel, grid, dim3(kTiledThreads), 0, s, a);
+    } else if (p.tiled) {
         const dim3 grid(2u * a.st.Hkv, (unsigned)((rows + kTileRows - 1) / kTileRows), p.k_splits);
         if (a.st.head_dim == 128)
             hipLaunchKernelGGL(project_append_tiled_kernel<128>, grid, dim3(kTiledThreads), 0, s, a);

@@ -43,7 +43,20 @@ def _bf16_round(a):
                                                             (8, 2, 128, 2048, 2, 40, True), (8, 2, 64, 4096, 3, 50, True),
                                                             (4, 1, 128, 2048, 5, 60, False), (8, 2, 128, 1536, 2, 17, True)])
 def test_project_append_parity(kb, Hq, Hkv, d, hidden, B, T_new, rope):
-    L, cap = 3, 160
+    _check_project_append(kb, Hq, Hkv, d, hidden, B, T_new, rope, 160)
+
+
+# Enough 256-row tiles that a workgroup takes two head blocks at once (K|K, K|V with an odd number
+# of kv heads, V|V): contractions of two and of six staged steps, a ragged last row tile.
+@pytest.mark.parametrize("Hq,Hkv,d,hidden,B,T_new,rope", [(8, 8, 128, 384, 24, 250, True), (3, 3, 128, 128, 64, 255, True),
+                                                            (8, 8, 128, 128, 25, 256, False)])
+def test_project_append_parity_two_heads_per_workgroup(kb, Hq, Hkv, d, hidden, B, T_new, rope):
+    assert Hkv * ((B * T_new + 255) // 256) >= 192
+    _check_project_append(kb, Hq, Hkv, d, hidden, B, T_new, rope, 272)
+
+
+def _check_project_append(kb, Hq, Hkv, d, hidden, B, T_new, rope, cap):
+    L = 3
     share = np.array([0, 1, 1], np.int32)
     table = inputs.make_block_table(B, cap // 16, B * cap // 16 + 2, 61)
     store = kb.KVStore(share, Hq, Hkv, d, "bf16", B * cap // 16 + 2, cap // 16, block_table=table, zero_fill=True)
