@@ -213,10 +213,20 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int quad = lane >> 4, l16 = lane & 15;
     const int wm = wave >> 1, wn = wave & 1;
-    const int head = blockIdx.x % st.Hkv;
-    const int is_v = blockIdx.x / st.Hkv;
+    // Workgroups go to the eight XCDs round-robin by their linear index, and each XCD has its own
+    // L2.  The grid is (8, tiles per XCD, splits), so blockIdx.x is the XCD; the output tiles,
+    // listed row tile by row tile, are dealt out in eight consecutive runs: the head blocks of a
+    // row tile meet in one L2 and fetch its x rows from memory once.
+    const int n_blocks = 2 * st.Hkv;
     const int M = a.B * a.T;
-    const int m0 = blockIdx.y * kTileRows;
+    const int n_row_tiles = (M + kTileRows - 1) / kTileRows;
+    const int tile = blockIdx.x * gridDim.y + blockIdx.y;
+    if (tile >= n_blocks * n_row_tiles) return;                    // padding of the last run
+    const int head_block = tile % n_blocks;
+    const int row_tile = tile / n_blocks;
+    const int head = head_block % st.Hkv;
+    const int is_v = head_block / st.Hkv;
+    const int m0 = row_tile * kTileRows;
 
     __shared__ __attribute__((aligned(16))) unsigned short sa[3][kTileRows][kLdsRow];
     __shared__ __attribute__((aligned(16))) unsigned short sb[3][D][kLdsRow];
@@ -368,8 +378,8 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
 
     // lane holds, of tile (i, j), column l16 and rows 4*quad .. 4*quad+3
     if (a.k_splits > 1) {
-        const size_t tile_id = (size_t)blockIdx.x * gridDim.y + blockIdx.y;
-        const size_t n_tiles = (size_t)gridDim.x * gridDim.y;
+        const size_t tile_id = (size_t)head_block * n_row_tiles + row_tile;
+        const size_t n_tiles = (size_t)n_blocks * n_row_tiles;
         constexpr int kPairs = 4 * NT * 2;                         // 64-bit pieces of a thread's accumulators
         unsigned long long* mine = reinterpret_cast<unsigned long long*>(a.partials) +
                                    (blockIdx.z * n_tiles + tile_id) * (size_t)(kPairs * kTiledThreads) + threadIdx.x;
@@ -472,16 +482,14 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_pair_kernel(Proj
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int quad = lane >> 4, l16 = lane & 15;
     const int wm = wave >> 2, wn = wave & 3;
-    // Workgroups go to the eight XCDs round-robin by their linear index, and each XCD has its own
-    // L2.  Index i is therefore read as (XCD i % 8, place i / 8 in it), and an XCD is given whole
-    // row tiles with all their head pairs: the x rows are then fetched into one L2 once and hit
-    // there by the other pairs' workgroups, which run at the same time.
+    // grid (8, tiles per XCD): blockIdx.x is the XCD, which takes a run of consecutive output
+    // tiles of the list ordered row tile by row tile (see the kernel above)
     const int n_pairs = st.Hkv;
-    const int place = blockIdx.x >> 3, xcd = blockIdx.x & 7;
-    const int pair = place % n_pairs;
-    const int row_tile = (place / n_pairs) * 8 + xcd;
     const int M = a.B * a.T;
-    if (row_tile * kTileRows >= M) return;                         // padding of the last group of eight row tiles
+    const int tile = blockIdx.x * gridDim.y + blockIdx.y;
+    if (tile >= n_pairs * ((M + kTileRows - 1) / kTileRows)) return;   // padding of the last run
+    const int pair = tile % n_pairs;
+    const int row_tile = tile / n_pairs;
     const int hb = pair * 2 + (wn >> 1);                           // this wavefront's head block
     const int strip = wn & 1;
     const int is_v = hb >= st.Hkv;
@@ -705,11 +713,10 @@ int launch_project_append(ProjectArgs a, void* workspace, void* stream)
     a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(p.tiles));
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (p.pair) {
-        const unsigned row_tiles = (unsigned)((rows + kTileRows - 1) / kTileRows);
-        const dim3 grid((row_tiles + 7) / 8 * 8 * a.st.Hkv, 1, 1);
+        const dim3 grid(8, (unsigned)((p.tiles + 7) / 8), 1);
         hipLaunchKernelGGL(project_append_pair_kernel, grid, dim3(kTiledThreads), 0, s, a);
     } else if (p.tiled) {
-        const dim3 grid(2u * a.st.Hkv, (unsigned)((rows + kTileRows - 1) / kTileRows), p.k_splits);
+        const dim3 grid(8, (unsigned)((p.tiles + 7) / 8), p.k_splits);
         if (a.st.head_dim == 128)
             hipLaunchKernelGGL(project_append_tiled_kernel<128>, grid, dim3(kTiledThreads), 0, s, a);
         else
