@@ -16,12 +16,12 @@
 // (same no-wait protocol as the attention splits).
 //
 // A prefill chunk (more than 32 rows) is a matrix product bounded by the matrix cores and takes
-// the tiled kernel instead: a workgroup of eight wavefronts owns 256 rows and one whole head of
-// K or V; the 256 x 64 pieces of x and 128 x 64 pieces of the head's weight rows go from global
-// memory straight into LDS (global_load_lds_dwordx4), three buffers deep, with the 16-byte pieces
+// a tiled kernel instead: a workgroup of eight wavefronts owns 256 rows and one whole head of
+// K or V (or, with enough rows, two adjacent heads); the 256 x 64 pieces of x and of the weight
+// rows go from global memory straight into LDS (global_load_lds_dwordx4), with the 16-byte pieces
 // of a row XOR-swizzled by the row index so that the operand reads of a wavefront fall on
-// distinct banks without padding; each wavefront keeps a 64 x (head_dim/2) block of accumulators
-// whose columns again hold both ends of the rotary pairs.
+// distinct banks without padding; each wavefront keeps a block of accumulators whose columns
+// again hold both ends of the rotary pairs.
 #include <hip/hip_runtime.h>
 
 #include "kvs_internal.h"
