@@ -711,7 +711,9 @@ void attn_bf16_wide_kernel(AttnArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int quad = lane >> 4, col = lane & 15;
-    const int g = blockIdx.x, b = blockIdx.y, cblk = blockIdx.z;
+    // later column blocks see more keys (causality) and run longer: they are started first, so
+    // that the launch does not end on its longest workgroups
+    const int g = blockIdx.x, b = blockIdx.y, cblk = gridDim.z - 1 - blockIdx.z;
     const int group = st.Hq / st.Hkv;
     const int ncols = a.T_new * group;
     const int cap = st.max_blocks_per_seq * kPageTokens;
