@@ -775,8 +775,8 @@ void attn_bf16_wide_kernel(AttnArgs a)
 #define KVS_FETCH_PAIR(pair, slot_)                                                                   \
     _Pragma("unroll") for (int pg = 0; pg < 2; ++pg) {                                                \
         int page = 2 * (pair) + pg;                                                                   \
-        page = page < wg_pages ? page : wg_pages - 1;        /* an absent second page: nobody reads it */ \
-        const u32x4* src = reinterpret_cast<const u32x4*>(pool + page_offset(st, slot, safe_block_of(st, b, page), g)); \
+        page = page < wg_pages ? page : (wg_pages > 0 ? wg_pages - 1 : 0);   /* past the end: a page nobody reads */ \
+        const u32x4* src = reinterpret_cast<const u32x4*>(pool + page_offset(st, slot, safe_block_of_uniform(st, b, page), g)); \
         _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                         \
             const int v = i * kWideThreads + (int)threadIdx.x;                                        \
             if (kPageVecs % kWideThreads == 0 || v < kPageVecs)                                       \
@@ -813,19 +813,33 @@ void attn_bf16_wide_kernel(AttnArgs a)
         for (int c = 0; c < DT; ++c) o[ct][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
+    // Fetches, LDS writes and barriers are unconditional and the loop runs whole rounds of kDepth
+    // pairs (past a workgroup's last pair its last page is fetched again and never read): straight-
+    // line code with a fixed number of loads per step, so that the compiler's waits name exactly the
+    // loads they need.  With a branch around any of them it must assume the fewest loads in flight
+    // and waits for all of them, which undoes the prefetch.
+    constexpr bool kStraight = NT > 1;                             // (the small variant measured faster with the branches)
 #pragma unroll
     for (int j = 0; j < kDepth; ++j)
-        if (j < wg_pairs) { KVS_FETCH_PAIR(j, j) }
-    if (wg_pairs > 0) {
+        if (kStraight || j < wg_pairs) { KVS_FETCH_PAIR(j, j) }
+    if (kStraight || wg_pairs > 0) {
         KVS_PUT_PAIR(0, 0)
-        if (kDepth < wg_pairs) { KVS_FETCH_PAIR(kDepth, 0) }
+        if (kStraight || kDepth < wg_pairs) { KVS_FETCH_PAIR(kDepth, 0) }
     }
+    // The query fragments are waited for here, once, and not inside the loop (where the compiler,
+    // which cannot see that a wavefront without keys never uses them, would otherwise put the wait:
+    // it would drain the page loads in flight).
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[ct][ks]));
     __syncthreads();
-    for (int p0 = 0; p0 < wg_pairs; p0 += kDepth) {
+    const int n_rounds = (wg_pairs + kDepth - 1) / kDepth;
+    for (int p0 = 0; p0 < n_rounds * kDepth; p0 += kDepth) {
 #pragma unroll
         for (int j = 0; j < kDepth; ++j) {
             const int pair = p0 + j;
-            if (pair < wg_pairs) {                                     // uniform over the workgroup
+            if (kStraight || pair < wg_pairs) {
                 const int buf = j & 1;                                 // kDepth is even
                 const int tok_a = 2 * pair * kPageTokens, tok_b = tok_a + kPageTokens;
                 if (tok_a < n_max) {
@@ -860,9 +874,9 @@ void attn_bf16_wide_kernel(AttnArgs a)
                         pair_values<D, NT>(va, vb, have_b, tok_a, tok_b, n_max, quad, pf, o);
                     }
                 }
-                if (pair + 1 < wg_pairs) {
+                if (kStraight || pair + 1 < wg_pairs) {
                     KVS_PUT_PAIR(buf ^ 1, (j + 1) % kDepth)            // that buffer was last read before the previous barrier
-                    if (pair + 1 + kDepth < wg_pairs) { KVS_FETCH_PAIR(pair + 1 + kDepth, (j + 1) % kDepth) }
+                    if (kStraight || pair + 1 + kDepth < wg_pairs) { KVS_FETCH_PAIR(pair + 1 + kDepth, (j + 1) % kDepth) }
                 }
                 __syncthreads();
             }

@@ -34,6 +34,18 @@ __device__ __forceinline__ int safe_block_of(const StoreView& st, int b, int pag
     return blk < 0 ? 0 : (blk >= st.num_blocks ? st.num_blocks - 1 : blk);
 }
 
+// The same for a page index that is uniform over the wavefront, as a scalar load whatever the
+// compiler can prove about the stores around it: the table is read through the constant address
+// space (no launch writes it).  A vector load would join the queue of the page loads in flight,
+// and waiting for it would drain them.
+__device__ __forceinline__ int safe_block_of_uniform(const StoreView& st, int b, int page)
+{
+    typedef const int __attribute__((address_space(4))) * table_ptr;
+    const size_t idx = (size_t)b * st.max_blocks_per_seq + page;
+    const int blk = st.block_table ? reinterpret_cast<table_ptr>(reinterpret_cast<size_t>(st.block_table))[idx] : (int)idx;
+    return blk < 0 ? 0 : (blk >= st.num_blocks ? st.num_blocks - 1 : blk);
+}
+
 // Element offset of the K page of (slot, block, kv head); the V page follows it.
 __device__ __forceinline__ size_t page_offset(const StoreView& st, int slot, int blk, int g)
 {
