@@ -688,13 +688,15 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 // 64 columns and lets its wavefronts share out the pages, so every 64 columns stream the whole
 // prefix again: 64 flops per byte, which the memory system, not the matrix cores, then bounds.
 // Here the wavefronts of a workgroup each take their own columns (256 per workgroup as 8 x 32, or
-// 64 as 4 x 16 when a head has fewer) and all consume the same page pair: the pair is fetched once per workgroup (each thread a few 16-byte pieces, one
-// pair ahead, in registers) and laid into LDS in operand order: keys as the plain image of the
-// two pages (the in-page order is the operand order, so a lane's operand is the 16 bytes at its
-// own index), values with the two pages' halves interleaved, so that a lane reads the eight-token
-// operand of the value product in one piece; each wavefront reads them back after a barrier.  A wavefront owns its columns for the whole context:
-// no state is merged, no splits, the output is written normalised.  Causality: a wavefront
-// skips the pairs that lie beyond the last key any of its columns sees.
+// 64 as 4 x 16 when a head has fewer) and all consume the same page pair.  The pair is fetched
+// once per workgroup (each thread a few 16-byte pieces, a few pairs ahead, in registers) and laid
+// into LDS in operand order: keys as the plain image of the two pages (the in-page order is the
+// operand order, so a lane's operand is the 16 bytes at its own index); values the same in the
+// small variant, and in the large one with the two pages' halves interleaved, so that a lane reads
+// the eight-token operand of the value product in one piece.  Each wavefront reads them back after
+// a barrier.  A wavefront owns its columns for the whole context: no state is merged, no splits,
+// the output is written normalised.  Causality: a wavefront skips the pairs that lie beyond the
+// last key any of its columns sees.
 // NT 16-column tiles per wavefront, WAVES wavefronts: NT * 16 * WAVES columns per workgroup.
 template <int D, int NT, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3 : 2)))
