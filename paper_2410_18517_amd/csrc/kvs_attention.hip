@@ -698,7 +698,11 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 // the output is written normalised.  Causality: a wavefront skips the pairs that lie beyond the
 // last key any of its columns sees.
 // NT 16-column tiles per wavefront, WAVES wavefronts: NT * 16 * WAVES columns per workgroup.
-template <int D, int NT, int WAVES>
+// kReadOnce: one column block per (sequence, kv head), so that every page is read exactly once per
+// launch and is streamed past the caches (nontemporal loads); with several blocks the later ones
+// find it in L2.  A template parameter, not a test of the grid size inside the kernel: a load
+// chosen by a run-time condition between the two kinds is folded into one plain load.
+template <int D, int NT, int WAVES, bool kReadOnce>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3 : 2)))
 void attn_bf16_wide_kernel(AttnArgs a)
 {
@@ -768,9 +772,6 @@ void attn_bf16_wide_kernel(AttnArgs a)
     constexpr int kDepth = NT == 1 ? 2 : 4;                        // fewer registers where occupancy matters more
     constexpr int kPasses = (kPageVecs + kWideThreads - 1) / kWideThreads;   // passes of the workgroup over one page
     u32x4 stage[kDepth][2 * kPasses];
-    // With one column block per (sequence, kv head) every page is read exactly once per launch and
-    // is streamed past the caches; with several, the later blocks find it in L2.
-    const bool read_once = gridDim.z == 1;
     // Each page of the pair is copied by whole passes of the workgroup, so that the page index --
     // and with it the page-table entry -- is the same for every thread of a pass: a scalar load,
     // which does not queue behind the vector loads already in flight.
@@ -782,7 +783,7 @@ void attn_bf16_wide_kernel(AttnArgs a)
         _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                         \
             const int v = i * kWideThreads + (int)threadIdx.x;                                        \
             if (kPageVecs % kWideThreads == 0 || v < kPageVecs)                                       \
-                stage[slot_][pg * kPasses + i] = read_once ? __builtin_nontemporal_load(src + v) : src[v]; \
+                stage[slot_][pg * kPasses + i] = kReadOnce ? __builtin_nontemporal_load(src + v) : src[v];  \
         }                                                                                             \
     }
 #define KVS_PUT_PAIR(buf, slot_)                                                                      \
@@ -865,7 +866,7 @@ void attn_bf16_wide_kernel(AttnArgs a)
     // that a wavefront without keys never uses them and would wait for them inside it).  The last
     // pairs take the same step with its branches.
     // (Only in the 8-wavefront variant: the small one, bound by HBM and not by its own latencies,
-    // measured 146 us with exact waits against 135 us with the draining ones on the 64-row chunk.)
+    // measured 128 us with exact waits against 122 us with the draining ones on the 64-row chunk.)
     const int n_straight = NT > 1 && wg_pairs > kDepth + 1 ? (wg_pairs - kDepth - 1) / kDepth * kDepth : 0;
     if (n_straight > 0) {
 #pragma unroll
@@ -923,12 +924,18 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
         // Enough columns per (sequence, kv head) to share every page among eight wavefronts, and
         // enough such workgroups to cover the chip without splitting the context.
         dim3 grid(a.st.Hkv, a.B, (ncols + 255) / 256);
-        hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8>), grid, dim3(512), 0, s, a);
+        if (grid.z == 1)
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, true>), grid, dim3(512), 0, s, a);
+        else
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, false>), grid, dim3(512), 0, s, a);
     } else if (!kFp8 && ncols >= 64 && (long)a.st.Hkv * a.B * ((ncols + 63) / 64) >= 512) {
         // Fewer columns: 16 per wavefront, four wavefronts; small enough in registers for several
         // workgroups per compute unit to hide each other's softmax arithmetic.
         dim3 grid(a.st.Hkv, a.B, (ncols + 63) / 64);
-        hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4>), grid, dim3(256), 0, s, a);
+        if (grid.z == 1)
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4, true>), grid, dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4, false>), grid, dim3(256), 0, s, a);
     } else {
         const int cgroups = (a.T_new * group + 63) / 64;
         dim3 grid(a.st.Hkv, a.B, a.n_splits * cgroups);
