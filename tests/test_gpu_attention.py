@@ -221,6 +221,36 @@ def test_shared_page_prefill_kernels(kb, d, Hq, Hkv, B, T_new):
     assert rel_l2_rows(short, got[:, -tail:].astype(np.float64)).max() <= REL_L2_ATTENTION
 
 
+@pytest.mark.parametrize("Hq,Hkv,B,T_new", [(16, 8, 16, 160),      # 320 columns: the 8-wavefront shared-page kernel
+                                            (8, 8, 64, 80)])       # 80 columns: the 4-wavefront one
+def test_shared_page_prefill_rising_scores(kb, Hq, Hkv, B, T_new):
+    """Keys that grow along the context in the direction of the queries: in the shared-page kernels
+    the reference of the exponentials then moves again and again (the accumulators are rescaled on
+    most page pairs), by steps from small to large, up to the causal edge of every row."""
+    d, cap = 128, 400
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, 2, Hq, Hkv, d, B, "bf16", cap, share, paged=True, seed=53)
+    rng = np.random.default_rng(53)
+    start = rng.integers(0, cap - T_new + 1, size=B).astype(np.int32)
+    start[0], start[-1] = 0, cap - T_new
+    u = inputs.normal((1, 1, 1, d), 53, 777).float()
+    u = u / u.norm()
+    for gain in (3.0, 40.0):
+        ramp = torch.linspace(0.0, 1.0, cap).view(1, cap, 1, 1)
+        k = torch.from_numpy(case.K[0].view(np.int16)).view(torch.bfloat16).float() * 0.05 + gain * ramp * u
+        k = k.to(torch.bfloat16).contiguous()
+        v = torch.from_numpy(case.V[0].view(np.int16)).view(torch.bfloat16).contiguous()
+        assert kb.kvs_append_kv(case.store, 0, k.cuda(), v.cuda(), np.zeros(B, np.int32)) == kb.KVS_OK
+        q = (inputs.normal((B, T_new, Hq, d), 53, 778).float() * 0.05 + 4.0 * u.view(1, 1, 1, d)).to(torch.bfloat16)
+        got = kb.kvs_prefill_attention(case.store, 1, q.cuda(), start).cpu().numpy()
+        assert np.isfinite(got).all()
+        Ko = [inputs.to_oracle_array(k), None]
+        for b in (0, B // 2, B - 1):
+            want = orc.shared_attention(1, share, [Ko[0][b:b + 1], None], [case.V[0][b:b + 1], None],
+                                        inputs.to_oracle_array(q[b:b + 1]), start[b:b + 1])
+            assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, (gain, b)
+
+
 def test_randomised_shapes_maps_and_lengths(kb):
     """Seeded sweep over store types, head groupings, batch sizes, sharing maps, paging, split sizes
     and ragged lengths; every case is compared element by element with the oracle."""
