@@ -163,20 +163,29 @@ __device__ __forceinline__ void widen4(unsigned w, unsigned& lo, unsigned& hi)
     hi = __builtin_bit_cast(unsigned, __builtin_convertvector(b, bf16x2));
 }
 
+// One 16-byte piece of an fp8 page -> the two 16-byte pieces of the bf16 page it stands for (same
+// lane, consecutive 64-piece blocks).  Keys: words x, y are one contraction step (channels
+// 8*quad .. +3, then +4 .. +7), words z, w the next.  Values: channel tiles 2s and 2s + 1 (tokens
+// 4*quad .. +3 each) in x, y, the next two in z, w.
+__device__ __forceinline__ void widen_piece(const u32x4 raw, u32x4& first, u32x4& second)
+{
+    unsigned a0, a1, b0, b1;
+    widen4(raw.x, a0, a1);
+    widen4(raw.y, b0, b1);
+    first = u32x4{a0, a1, b0, b1};
+    widen4(raw.z, a0, a1);
+    widen4(raw.w, b0, b1);
+    second = u32x4{a0, a1, b0, b1};
+}
+
 // fp8 page registers -> the bf16 operand registers the arithmetic below works on.
 template <int D>
 __device__ __forceinline__ void widen(const PageRegs8<D>& r, PageRegs<D>& o)
 {
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) {
-        const u32x4 kk = r.k[s >> 1], vv = r.v[s >> 1];
-        unsigned a0, a1, b0, b1;
-        widen4((s & 1) ? kk.z : kk.x, a0, a1);        // channels 8*quad .. +3 of step s, then +4 .. +7
-        widen4((s & 1) ? kk.w : kk.y, b0, b1);
-        o.k[s] = u32x4{a0, a1, b0, b1};
-        widen4((s & 1) ? vv.z : vv.x, a0, a1);        // channel tile 2s: tokens 4*quad .. +3
-        widen4((s & 1) ? vv.w : vv.y, b0, b1);        // channel tile 2s + 1
-        o.v[s] = u32x4{a0, a1, b0, b1};
+    for (int s = 0; s < D / 64; ++s) {
+        widen_piece(r.k[s], o.k[2 * s], o.k[2 * s + 1]);
+        widen_piece(r.v[s], o.v[2 * s], o.v[2 * s + 1]);
     }
 }
 
@@ -702,7 +711,10 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 // launch and is streamed past the caches (nontemporal loads); with several blocks the later ones
 // find it in L2.  A template parameter, not a test of the grid size inside the kernel: a load
 // chosen by a run-time condition between the two kinds is folded into one plain load.
-template <int D, int NT, int WAVES, bool kReadOnce>
+// kFp8: the slots hold E4M3 bytes.  A page is fetched as it is stored (half the bytes, half the
+// registers in flight) and widened to bf16 once, by the thread that lays it into LDS; LDS holds the
+// bf16 page and everything downstream is the same code.
+template <int D, int NT, int WAVES, bool kReadOnce, bool kFp8>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3 : 2)))
 void attn_bf16_wide_kernel(AttnArgs a)
 {
@@ -712,7 +724,8 @@ void attn_bf16_wide_kernel(AttnArgs a)
     // register shuffling before the value product); the small one, tight on registers at three
     // wavefronts per SIMD, keeps the plain page image and concatenates in registers.
     constexpr bool kCatV = NT > 1;
-    constexpr int kPageVecs = kPageTokens * D * 2 * 2 / 16;        // 16-byte pieces of one page (K then V)
+    constexpr int kPageVecs = kPageTokens * D * 2 * 2 / 16;        // 16-byte pieces of one bf16 page (K then V)
+    constexpr int kRawVecs = kFp8 ? kPageVecs / 2 : kPageVecs;     // and of the page as the store holds it
     const StoreView& st = a.st;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -765,12 +778,13 @@ void attn_bf16_wide_kernel(AttnArgs a)
     const int wg_pairs = (wg_pages + 1) / 2;
 
     __shared__ u32x4 tile[2][2 * kPageVecs];
-    const unsigned short* pool = static_cast<const unsigned short*>(st.pool);
+    using Elem = std::conditional_t<kFp8, unsigned char, unsigned short>;   // page_offset counts elements
+    const Elem* pool = static_cast<const Elem*>(st.pool);
     // kDepth page pairs are in flight from global memory to registers at any time (a workgroup
     // walks its pairs one after another, so the bytes it keeps in flight are all that hides the
     // memory latency); slot k of `stage` holds the pairs with index = k mod kDepth.
     constexpr int kDepth = NT == 1 ? 2 : 4;                        // fewer registers where occupancy matters more
-    constexpr int kPasses = (kPageVecs + kWideThreads - 1) / kWideThreads;   // passes of the workgroup over one page
+    constexpr int kPasses = (kRawVecs + kWideThreads - 1) / kWideThreads;    // passes of the workgroup over one page
     u32x4 stage[kDepth][2 * kPasses];
     // Each page of the pair is copied by whole passes of the workgroup, so that the page index --
     // and with it the page-table entry -- is the same for every thread of a pass: a scalar load,
@@ -782,25 +796,40 @@ void attn_bf16_wide_kernel(AttnArgs a)
         const u32x4* src = reinterpret_cast<const u32x4*>(pool + page_offset(st, slot, safe_block_of_uniform(st, b, page), g)); \
         _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                         \
             const int v = i * kWideThreads + (int)threadIdx.x;                                        \
-            if (kPageVecs % kWideThreads == 0 || v < kPageVecs)                                       \
+            if (kRawVecs % kWideThreads == 0 || v < kRawVecs)                                         \
                 stage[slot_][pg * kPasses + i] = kReadOnce ? __builtin_nontemporal_load(src + v) : src[v];  \
+        }                                                                                             \
+    }
+    // bf16 piece `v_` of page pg (0 / 1) of a pair into its place in tile[buf]
+#define KVS_STORE_PIECE(buf, pg, v_, piece_)                                                          \
+    {                                                                                                 \
+        const int vv = (v_);                                                                          \
+        const u32x4 pc = (piece_);                                                                    \
+        if (!kCatV) {                                            /* the page as it is */              \
+            tile[buf][(pg) * kPageVecs + vv] = pc;                                                    \
+        } else if (vv < KS * 64) {                               /* a key piece: the page's own order */ \
+            tile[buf][(pg) * KS * 64 + vv] = pc;                                                      \
+        } else {                                                 /* a value piece: halves to two pair operands */ \
+            const int vs = (vv - KS * 64) >> 6, vl = vv & 63;                                         \
+            u32x2* dst = reinterpret_cast<u32x2*>(&tile[buf][2 * KS * 64 + (2 * vs) * 64 + vl]) + (pg); \
+            dst[0] = u32x2{pc.x, pc.y};                                                               \
+            dst[2 * 64] = u32x2{pc.z, pc.w};                                                          \
         }                                                                                             \
     }
 #define KVS_PUT_PAIR(buf, slot_)                                                                      \
     _Pragma("unroll") for (int pg = 0; pg < 2; ++pg)                                                  \
         _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                         \
             const int v = i * kWideThreads + (int)threadIdx.x;                                        \
-            if (kPageVecs % kWideThreads == 0 || v < kPageVecs) {                                     \
-                const u32x4 piece = stage[slot_][pg * kPasses + i];                                   \
-                if (!kCatV) {                                    /* the page as it is */              \
-                    tile[buf][pg * kPageVecs + v] = piece;                                            \
-                } else if (v < KS * 64) {                        /* a key piece: the page's own order */ \
-                    tile[buf][pg * KS * 64 + v] = piece;                                              \
-                } else {                                         /* a value piece: halves to two pair operands */ \
-                    const int vs = (v - KS * 64) >> 6, vl = v & 63;                                   \
-                    u32x2* dst = reinterpret_cast<u32x2*>(&tile[buf][2 * KS * 64 + (2 * vs) * 64 + vl]) + pg; \
-                    dst[0] = u32x2{piece.x, piece.y};                                                 \
-                    dst[2 * 64] = u32x2{piece.z, piece.w};                                            \
+            if (kRawVecs % kWideThreads == 0 || v < kRawVecs) {                                       \
+                const u32x4 raw = stage[slot_][pg * kPasses + i];                                     \
+                if constexpr (kFp8) {                            /* raw block r -> bf16 blocks 2r, 2r + 1 */ \
+                    u32x4 w0, w1;                                                                     \
+                    widen_piece(raw, w0, w1);                                                         \
+                    const int at0 = (v >> 6) * 128 + (v & 63);                                        \
+                    KVS_STORE_PIECE(buf, pg, at0, w0)                                                 \
+                    KVS_STORE_PIECE(buf, pg, at0 + 64, w1)                                            \
+                } else {                                                                              \
+                    KVS_STORE_PIECE(buf, pg, v, raw)                                                  \
                 }                                                                                     \
             }                                                                                         \
         }
@@ -899,6 +928,7 @@ void attn_bf16_wide_kernel(AttnArgs a)
 #undef KVS_WIDE_STEP
 #undef KVS_FETCH_PAIR
 #undef KVS_PUT_PAIR
+#undef KVS_STORE_PIECE
 
     // lane holds channels c*16 + 4*quad .. +3 of its column in o[ct][c]
 #pragma unroll
@@ -920,22 +950,22 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
     if (a.T_new == 1) {
         dim3 grid(a.st.Hkv, a.B, a.n_splits);
         hipLaunchKernelGGL((attn_bf16_kernel<D, 1, 4, kFp8>), grid, dim3(kThreads), 0, s, a);
-    } else if (const int ncols = a.T_new * group; !kFp8 && ncols >= 256 && (long)a.st.Hkv * a.B * ((ncols + 255) / 256) >= 256) {
+    } else if (const int ncols = a.T_new * group; ncols >= 256 && (long)a.st.Hkv * a.B * ((ncols + 255) / 256) >= 256) {
         // Enough columns per (sequence, kv head) to share every page among eight wavefronts, and
         // enough such workgroups to cover the chip without splitting the context.
         dim3 grid(a.st.Hkv, a.B, (ncols + 255) / 256);
         if (grid.z == 1)
-            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, true>), grid, dim3(512), 0, s, a);
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, true, kFp8>), grid, dim3(512), 0, s, a);
         else
-            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, false>), grid, dim3(512), 0, s, a);
-    } else if (!kFp8 && ncols >= 64 && (long)a.st.Hkv * a.B * ((ncols + 63) / 64) >= 512) {
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, false, kFp8>), grid, dim3(512), 0, s, a);
+    } else if (ncols >= 64 && (long)a.st.Hkv * a.B * ((ncols + 63) / 64) >= 512) {
         // Fewer columns: 16 per wavefront, four wavefronts; small enough in registers for several
         // workgroups per compute unit to hide each other's softmax arithmetic.
         dim3 grid(a.st.Hkv, a.B, (ncols + 63) / 64);
         if (grid.z == 1)
-            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4, true>), grid, dim3(256), 0, s, a);
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4, true, kFp8>), grid, dim3(256), 0, s, a);
         else
-            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4, false>), grid, dim3(256), 0, s, a);
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4, false, kFp8>), grid, dim3(256), 0, s, a);
     } else {
         const int cgroups = (a.T_new * group + 63) / 64;
         dim3 grid(a.st.Hkv, a.B, a.n_splits * cgroups);

@@ -101,3 +101,33 @@ def test_decode_step_and_prefill_over_fp8_slots(kb):
     with pytest.raises(kb.KvsError) as err:
         kb.kvs_compact_kv(case.store, 0, np.zeros((B, Hkv, 4), np.int32), np.ones((B, Hkv), np.int32))
     assert err.value.status == kb.KVS_ERR_UNSUPPORTED
+
+
+# Shapes that reach the shared-page prefill kernels over fp8 slots (see test_gpu_attention.py for
+# the rule): 8 wavefronts x 2 tiles, 4 wavefronts x 1 tile, both head sizes, one column block per
+# head (pages streamed past the caches) and several.
+@pytest.mark.parametrize("d,Hq,Hkv,B,T_new", [(128, 16, 8, 16, 150), (128, 8, 8, 32, 128), (128, 16, 8, 16, 100),
+                                              (64, 8, 8, 64, 64), (64, 8, 8, 16, 300)])
+def test_shared_page_prefill_over_fp8_slots(kb, d, Hq, Hkv, B, T_new):
+    L, cap = 2, 416
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, "fp8", cap, share, paged=True, seed=73)
+    rng = np.random.default_rng(73)
+    start = rng.integers(0, cap - T_new + 1, size=B).astype(np.int32)
+    start[0], start[-1] = 0, cap - T_new
+    q = case.q(1, rows=T_new)
+    got = kb.kvs_prefill_attention(case.store, 1, q.cuda(), start).cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in (0, B // 2, B - 1):
+        want = orc.shared_attention(1, share, [case.K[0][b:b + 1], None], [case.V[0][b:b + 1], None],
+                                    inputs.to_oracle_array(q[b:b + 1]), start[b:b + 1])
+        assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, b
+    # the same rows as a short chunk, which takes the page-splitting kernel: each is within the bar of
+    # the oracle (the short chunk is checked against it too), hence within twice the bar of the other
+    tail = 8
+    short = kb.kvs_prefill_attention(case.store, 1, q[:, -tail:].contiguous().cuda(), start + (T_new - tail)).cpu().numpy()
+    b = B - 1
+    want = orc.shared_attention(1, share, [case.K[0][b:b + 1], None], [case.V[0][b:b + 1], None],
+                                inputs.to_oracle_array(q[b:b + 1, -tail:].contiguous()), start[b:b + 1] + (T_new - tail))
+    assert rel_l2_rows(short[b:b + 1], want).max() <= REL_L2_ATTENTION
+    assert rel_l2_rows(short, got[:, -tail:].astype(np.float64)).max() <= 2 * REL_L2_ATTENTION
