@@ -155,9 +155,10 @@ int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const vo
  *     k = x . w_k^T,   v = x . w_v^T                      (fp32 accumulation)
  *     k[c], k[c+h] <- k[c] cos - k[c+h] sin,  k[c+h] cos + k[c] sin      h = head_dim/2, c < h,
  *          cos = rope_cos[p][c], sin = rope_sin[p][c], p = start_pos[b] + i  (skipped if NULL)
- *     rounded to bf16 (nearest even) and stored at position p of the layer's slot.
+ *     rounded to bf16 (nearest even) and stored at position p of the layer's slot (an fp8 store
+ *     rounds that bf16 value on to E4M3, as kvs_append_kv of the bf16 row would).
  * rope_cos, rope_sin: device fp32 [rope_positions][head_dim/2], rope_positions >= capacity.
- * bf16 stores only; hidden a multiple of 128.  workspace: device, >=
+ * bf16 and fp8 stores (x and the weights are bf16 either way); hidden a multiple of 128.  workspace: device, >=
  * kvs_project_workspace_bytes(), zero-filled once by the caller and left zero by every call
  * (it holds arrival counters and partial sums of the split contraction); calls sharing it must
  * not overlap.  Returns KVS_NOOP without touching the GPU when the layer reads a donor's cache.

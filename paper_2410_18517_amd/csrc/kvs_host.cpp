@@ -339,7 +339,7 @@ int kvs_project_append_kv(const kvs_store* store, int layer, const void* x, int 
     if (!x || !w_k || !w_v || !start_pos) return fail(KVS_ERR_INVALID_ARG, "x, w_k, w_v or start_pos is NULL");
     if ((rope_cos == nullptr) != (rope_sin == nullptr))
         return fail(KVS_ERR_INVALID_ARG, "rope_cos and rope_sin must be given together");
-    if (store->desc.dtype != KVS_BF16) return fail(KVS_ERR_UNSUPPORTED, "the fused projection needs a bf16 store");
+    if (store->desc.dtype == KVS_F32) return fail(KVS_ERR_UNSUPPORTED, "the fused projection needs a bf16 or fp8 store");
     if (hidden <= 0 || hidden % 128 != 0) return fail(KVS_ERR_UNSUPPORTED, "hidden must be a positive multiple of 128 (got %d)", hidden);
     if (B <= 0 || T_new <= 0) return fail(KVS_ERR_INVALID_ARG, "B and T_new must be positive (B=%d, T_new=%d)", B, T_new);
     const long capacity = (long)store->desc.max_blocks_per_seq * KVS_BLOCK_TOKENS;
@@ -372,8 +372,8 @@ int kvs_project_append_kv(const kvs_store* store, int layer, const void* x, int 
 size_t kvs_project_workspace_bytes(const kvs_desc* d, int hidden, int B, int T_new)
 {
     if (check_desc(d) != KVS_OK) return 0;
-    if (d->dtype != KVS_BF16 || hidden <= 0 || hidden % 128 != 0 || B <= 0 || T_new <= 0 || (long)B * T_new > (1L << 30)) {
-        fail(KVS_ERR_INVALID_ARG, "bf16 store, hidden a positive multiple of 128, B and T_new positive");
+    if (d->dtype == KVS_F32 || hidden <= 0 || hidden % 128 != 0 || B <= 0 || T_new <= 0 || (long)B * T_new > (1L << 30)) {
+        fail(KVS_ERR_INVALID_ARG, "bf16 or fp8 store, hidden a positive multiple of 128, B and T_new positive");
         return 0;
     }
     return kvs::project_workspace_bytes(d->Hkv, d->head_dim, hidden, B * T_new);

@@ -24,12 +24,12 @@
 // again hold both ends of the rotary pairs.
 #include <hip/hip_runtime.h>
 
+#include "kvs_device.h"
 #include "kvs_internal.h"
 
 namespace kvs {
 namespace {
 
-constexpr int kPageTokens = 16;
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int kUnroll = 4;             // contraction steps (of 32) whose loads are issued together
@@ -46,11 +46,16 @@ __device__ __forceinline__ unsigned short round_bf16(float x)
     return (unsigned short)(__builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2)) & 0xffffu);
 }
 
-// In-page element index of (token t, channel c): the store's operand order (see kvs.h).
-__device__ __forceinline__ int k_index(int t, int c) { return (((c >> 5) * 4 + ((c & 31) >> 3)) * 16 + t) * 8 + (c & 7); }
-__device__ __forceinline__ int v_index(int t, int c)
+// One projected element into its page (`page_off`: element offset of the page in the pool), in
+// the store's operand order.  bf16 store: rounded to bf16.  fp8 store: that bf16 value rounded on
+// to E4M3, exactly what an append of the bf16 row would store.
+__device__ __forceinline__ void store_projected(void* pool, size_t page_off, bool fp8, int is_v, int t, int c, float x)
 {
-    return ((((c >> 5) * 4 + (t >> 2)) * 16 + (c & 15)) * 2 + ((c >> 4) & 1)) * 4 + (t & 3);
+    const unsigned short h = round_bf16(x);
+    if (fp8)
+        static_cast<unsigned char*>(pool)[page_off + (is_v ? v_index_fp8(t, c) : k_index_fp8(t, c))] = (unsigned char)bf16_to_e4m3(h);
+    else
+        static_cast<unsigned short*>(pool)[page_off + (is_v ? v_index_bf16(t, c) : k_index_bf16(t, c))] = h;
 }
 
 __global__ __launch_bounds__(kThreads) void project_append_bf16_kernel(ProjectArgs a)
@@ -182,16 +187,11 @@ __global__ __launch_bounds__(kThreads) void project_append_bf16_kernel(ProjectAr
         lo = rl;
         hi = rh;
     }
-    unsigned short* page = static_cast<unsigned short*>(st.pool) +
-                           ((((size_t)slot * st.num_blocks + blk) * st.Hkv + head) * 2 + is_v) * (size_t)(kPageTokens * D);
+    const size_t page_off = ((((size_t)slot * st.num_blocks + blk) * st.Hkv + head) * 2 + is_v) * (size_t)(kPageTokens * D);
     const int t = (int)(pos % kPageTokens);
-    if (is_v) {
-        page[v_index(t, c0 + c)] = round_bf16(lo);
-        page[v_index(t, c0 + c + half)] = round_bf16(hi);
-    } else {
-        page[k_index(t, c0 + c)] = round_bf16(lo);
-        page[k_index(t, c0 + c + half)] = round_bf16(hi);
-    }
+    const bool fp8 = st.dtype == 2;                              // the store's type code: 1 bf16, 2 fp8
+    store_projected(st.pool, page_off, fp8, is_v, t, c0 + c, lo);
+    store_projected(st.pool, page_off, fp8, is_v, t, c0 + c + half, hi);
 }
 
 // ---- tiled kernel for many rows ------------------------------------------------------------
@@ -429,6 +429,7 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
     }
 
     const bool rotate = !is_v && a.rope_cos;
+    const bool fp8 = st.dtype == 2;                              // the store's type code: 1 bf16, 2 fp8
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -436,7 +437,6 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
             const int row = wm * 64 + i * 16 + quad * 4 + r;
             const long long off = row_page[row];                   // written before the first barrier
             const int pos = row_pos[row];
-            unsigned short* page = static_cast<unsigned short*>(st.pool) + (off < 0 ? 0 : off);
             const int t = pos % kPageTokens;
 #pragma unroll
             for (int j = 0; j < NT / 2; ++j) {
@@ -449,8 +449,8 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_tiled_kernel(Pro
                     hi = rh;
                 }
                 if (off >= 0) {
-                    page[is_v ? v_index(t, c) : k_index(t, c)] = round_bf16(lo);
-                    page[is_v ? v_index(t, c + half) : k_index(t, c + half)] = round_bf16(hi);
+                    store_projected(st.pool, (size_t)off, fp8, is_v, t, c, lo);
+                    store_projected(st.pool, (size_t)off, fp8, is_v, t, c + half, hi);
                 }
             }
         }
@@ -618,6 +618,7 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_pair_kernel(Proj
 
     // lane holds, of tile (i, j), column l16 and rows 4*quad .. 4*quad+3
     const bool rotate = !is_v && a.rope_cos;
+    const bool fp8 = st.dtype == 2;                              // the store's type code: 1 bf16, 2 fp8
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
@@ -625,8 +626,7 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_pair_kernel(Proj
             const int row = wm * 128 + i * 16 + quad * 4 + r;
             const long long rb = row_block[row];
             const int pos = row_pos[row];
-            unsigned short* page = static_cast<unsigned short*>(st.pool) +
-                                   (((size_t)(rb < 0 ? 0 : rb) * st.Hkv + head) * 2 + is_v) * (size_t)(kPageTokens * D);
+            const size_t page_off = (((size_t)(rb < 0 ? 0 : rb) * st.Hkv + head) * 2 + is_v) * (size_t)(kPageTokens * D);
             const int t = pos % kPageTokens;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -639,8 +639,8 @@ __global__ __launch_bounds__(kTiledThreads) void project_append_pair_kernel(Proj
                     hi = rh;
                 }
                 if (rb >= 0) {
-                    page[is_v ? v_index(t, c) : k_index(t, c)] = round_bf16(lo);
-                    page[is_v ? v_index(t, c + half) : k_index(t, c + half)] = round_bf16(hi);
+                    store_projected(st.pool, page_off, fp8, is_v, t, c, lo);
+                    store_projected(st.pool, page_off, fp8, is_v, t, c + half, hi);
                 }
             }
         }

@@ -55,11 +55,22 @@ def test_project_append_parity_two_heads_per_workgroup(kb, Hq, Hkv, d, hidden, B
     _check_project_append(kb, Hq, Hkv, d, hidden, B, T_new, rope, 272)
 
 
-def _check_project_append(kb, Hq, Hkv, d, hidden, B, T_new, rope, cap):
+# Into fp8 slots: the streaming kernel (with a split contraction), the tiled one and the one with
+# two head blocks per workgroup.  A stored element is the bf16-rounded result rounded on to E4M3:
+# within half an E4M3 step (2^-4 relative, 2^-10 below the normal range) plus the bf16 step of the
+# oracle's unrounded value, exactly an E4M3 value, and nearly always the very code the oracle's own
+# rounding chain gives (an accumulation error can only matter next to a rounding boundary).
+@pytest.mark.parametrize("Hq,Hkv,d,hidden,B,T_new,rope,cap", [(8, 2, 128, 2048, 3, 1, True, 160), (8, 2, 64, 1024, 3, 50, True, 160),
+                                                                (8, 8, 128, 384, 24, 250, True, 272)])
+def test_project_append_into_fp8_slots(kb, Hq, Hkv, d, hidden, B, T_new, rope, cap):
+    _check_project_append(kb, Hq, Hkv, d, hidden, B, T_new, rope, cap, dtype="fp8")
+
+
+def _check_project_append(kb, Hq, Hkv, d, hidden, B, T_new, rope, cap, dtype="bf16"):
     L = 3
     share = np.array([0, 1, 1], np.int32)
     table = inputs.make_block_table(B, cap // 16, B * cap // 16 + 2, 61)
-    store = kb.KVStore(share, Hq, Hkv, d, "bf16", B * cap // 16 + 2, cap // 16, block_table=table, zero_fill=True)
+    store = kb.KVStore(share, Hq, Hkv, d, dtype, B * cap // 16 + 2, cap // 16, block_table=table, zero_fill=True)
     x = (inputs.normal((B, T_new, hidden), 61, 0, dtype="f32") / 4).to(torch.bfloat16)
     wk = (inputs.normal((Hkv * d, hidden), 61, 1, dtype="f32") / np.sqrt(hidden)).to(torch.bfloat16)
     wv = (inputs.normal((Hkv * d, hidden), 61, 2, dtype="f32") / np.sqrt(hidden)).to(torch.bfloat16)
@@ -78,13 +89,24 @@ def _check_project_append(kb, Hq, Hkv, d, hidden, B, T_new, rope, cap):
     assert torch.equal(first, store.pool)
     want_k, want_v = project_kv(inputs.to_oracle_array(x), inputs.to_oracle_array(wk), inputs.to_oracle_array(wv),
                                 Hkv, d, start, cos, sin)
+    same, total = 0, 0
     for layer in (1, 2):                                         # the recipient sees the donor's new rows
         for b in range(B):
             k, v = kb.kvs_gather_kv(store, layer, int(start[b]), T_new, B)
             for got, want in ((k[b], want_k[b]), (v[b], want_v[b])):
                 got = got.float().cpu().numpy().astype(np.float64)
+                if dtype == "fp8":
+                    from oracle.fp8 import round_e4m3
+                    assert np.array_equal(got, round_e4m3(got))
+                    assert np.all(np.abs(got - want) <= (2.0 ** -4 + 2.0 ** -7) * np.abs(want) + 2.0 ** -10 + 2.0 ** -14), (layer, b)
+                    chain = round_e4m3(_bf16_round(want).float().numpy().astype(np.float64))
+                    same += int((got == chain).sum())
+                    total += got.size
+                    continue
                 floor = 1e-2 * np.sqrt((want ** 2).mean())
                 assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.maximum(np.abs(want), floor)), (layer, b)
+    if dtype == "fp8":
+        assert same >= 0.995 * total, (same, total)
     # slot 0 (layer 0) untouched
     k0, _ = kb.kvs_gather_kv(store, 0, 0, cap, B)
     assert float(k0.float().abs().max()) == 0.0
