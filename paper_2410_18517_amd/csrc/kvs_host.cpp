@@ -318,7 +318,6 @@ int kvs_compact_kv(const kvs_store* store, int layer, const int32_t* keep_idx, c
     if (!store->block_table && (long)B * store->desc.max_blocks_per_seq > store->desc.num_blocks)
         return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
     if (B > 65535) return fail(KVS_ERR_CAPACITY, "B is limited to 65535");
-    if (store->desc.dtype == KVS_FP8) return fail(KVS_ERR_UNSUPPORTED, "compaction of fp8 slots is not implemented");
     if (store->host_share_map[layer] != layer) return KVS_NOOP;   // its donor's compaction is the one it reads
     kvs::CompactArgs a;
     a.st = view_of(store, layer);

@@ -171,13 +171,16 @@ __global__ __launch_bounds__(256) void append_pages_bf16_kernel(CopyArgs a)
 // workgroup meets at a barrier, then the pieces are stored at chunk + t.  Because
 // keep_idx[j] >= j, a chunk reads only positions at or behind its own start and writes only its
 // own 128 positions, so chunks never touch each other's data and one barrier per chunk is enough.
+// kKind: the store's type code (0 fp32: a piece is 4 channels; 1 bf16, 2 fp8: 8 channels, whose keys
+// are one contiguous run in the page and whose values are eight separate elements).
 constexpr int kCompactTokens = 128;
-template <bool kBf16>
+template <int kKind>
 __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
 {
     const StoreView& st = a.st;
     const int D = st.head_dim;
-    constexpr int per = kBf16 ? 8 : 4;
+    constexpr bool kBf16 = kKind == 1, kFp8 = kKind == 2;
+    constexpr int per = kKind == 0 ? 4 : 8;
     const int g = blockIdx.x, b = blockIdx.y;
     const int ch = blockIdx.z * 2 + (threadIdx.x & 1);         // this thread's piece of the row
     const int tt = threadIdx.x >> 1;
@@ -206,6 +209,15 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) w[e >> 1] |= (unsigned)vp[v_index_bf16(ts, ch * 8 + e)] << ((e & 1) * 16);
                 vreg = make_uint4(w[0], w[1], w[2], w[3]);
+            } else if (kFp8) {
+                const unsigned char* kp = static_cast<const unsigned char*>(st.pool) + page_offset(st, slot, sblk, g);
+                const unsigned char* vp = kp + kPageTokens * D;
+                const uint2 k8 = *reinterpret_cast<const uint2*>(kp + k_index_fp8(ts, ch * 8));
+                kreg = make_uint4(k8.x, k8.y, 0, 0);
+                unsigned w[2] = {0, 0};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[e >> 2] |= (unsigned)vp[v_index_fp8(ts, ch * 8 + e)] << ((e & 3) * 8);
+                vreg = make_uint4(w[0], w[1], 0, 0);
             } else {
                 const float* kp = static_cast<const float*>(st.pool) + page_offset(st, slot, sblk, g) + (size_t)ts * D + ch * 4;
                 kreg = *reinterpret_cast<const uint4*>(kp);
@@ -221,6 +233,13 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
                 const unsigned w[4] = {vreg.x, vreg.y, vreg.z, vreg.w};
 #pragma unroll
                 for (int e = 0; e < 8; ++e) vp[v_index_bf16(td, ch * 8 + e)] = (unsigned short)(w[e >> 1] >> ((e & 1) * 16));
+            } else if (kFp8) {
+                unsigned char* kp = static_cast<unsigned char*>(st.pool) + page_offset(st, slot, dblk, g);
+                unsigned char* vp = kp + kPageTokens * D;
+                *reinterpret_cast<uint2*>(kp + k_index_fp8(td, ch * 8)) = make_uint2(kreg.x, kreg.y);
+                const unsigned w[2] = {vreg.x, vreg.y};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vp[v_index_fp8(td, ch * 8 + e)] = (unsigned char)(w[e >> 2] >> ((e & 3) * 8));
             } else {
                 float* kp = static_cast<float*>(st.pool) + page_offset(st, slot, dblk, g) + (size_t)td * D + ch * 4;
                 *reinterpret_cast<uint4*>(kp) = kreg;
@@ -250,12 +269,14 @@ int launch_append(const CopyArgs& a, void* stream)
 
 int launch_compact(const CompactArgs& a, void* stream)
 {
-    const int pieces = a.st.head_dim / (a.st.dtype == 1 ? 8 : 4);
+    const int pieces = a.st.head_dim / (a.st.dtype == 0 ? 4 : 8);
     const dim3 grid(a.st.Hkv, a.B, (pieces + 1) / 2);
     if (a.st.dtype == 1)
-        hipLaunchKernelGGL(compact_kernel<true>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+        hipLaunchKernelGGL(compact_kernel<1>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    else if (a.st.dtype == 2)
+        hipLaunchKernelGGL(compact_kernel<2>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
     else
-        hipLaunchKernelGGL(compact_kernel<false>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+        hipLaunchKernelGGL(compact_kernel<0>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
     return (int)hipGetLastError();
 }
 

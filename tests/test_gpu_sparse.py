@@ -48,7 +48,8 @@ def _pack(keep, B, Hkv):
 
 
 @pytest.mark.parametrize("dtype,d,Hq,Hkv,paged", [("bf16", 128, 8, 2, True), ("bf16", 64, 4, 4, False),
-                                                  ("f32", 64, 4, 2, True), ("f32", 256, 2, 1, True)])
+                                                  ("f32", 64, 4, 2, True), ("f32", 256, 2, 1, True),
+                                                  ("fp8", 128, 8, 2, True), ("fp8", 64, 4, 4, False)])
 def test_compaction_moves_the_kept_tokens_to_the_front(kb, dtype, d, Hq, Hkv, paged):
     L, B, cap, T = 3, 3, 208, 200
     share = np.array([0, 1, 1], np.int32)
