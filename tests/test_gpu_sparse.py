@@ -11,7 +11,7 @@ import torch
 
 from oracle.sparse import sparse_decode_attention, compact
 from paper_2410_18517_amd import inputs
-from helpers import Case, rel_l2_rows, REL_L2_ATTENTION
+from helpers import Case, rel_l2_rows, stored_fp8, REL_L2_ATTENTION
 
 pytestmark = pytest.mark.gpu
 
@@ -79,7 +79,7 @@ def test_compaction_moves_the_kept_tokens_to_the_front(kb, dtype, d, Hq, Hkv, pa
 
 
 @pytest.mark.parametrize("dtype,d,Hq,Hkv,split", [("bf16", 128, 8, 2, 0), ("bf16", 128, 8, 2, 64), ("bf16", 64, 8, 8, 0),
-                                                  ("f32", 64, 4, 2, 0)])
+                                                  ("f32", 64, 4, 2, 0), ("fp8", 128, 8, 2, 0), ("fp8", 64, 8, 8, 64)])
 def test_attention_over_kept_sets_matches_the_oracle(kb, dtype, d, Hq, Hkv, split):
     L, B, cap = 4, 3, 528
     share = np.array([0, 1, 0, 1], np.int32)                 # slots: layer 0 -> 0, layer 1 -> 1
@@ -93,7 +93,7 @@ def test_attention_over_kept_sets_matches_the_oracle(kb, dtype, d, Hq, Hkv, spli
         idx, cnt = _pack(keeps[donor], B, Hkv)
         assert kb.kvs_compact_kv(case.store, donor, idx, cnt) == kb.KVS_OK
         kv_lens[donor] = cnt
-    q = inputs.normal((B, Hq, d), 32, 900, dtype=dtype)
+    q = inputs.normal((B, Hq, d), 32, 900, dtype=case.row_dtype)
     assert kb.lib().kvs_set_split_tokens(split) == kb.KVS_OK
     try:
         for layer in range(L):
@@ -108,12 +108,13 @@ def test_attention_over_kept_sets_matches_the_oracle(kb, dtype, d, Hq, Hkv, spli
         assert kb.lib().kvs_set_split_tokens(0) == kb.KVS_OK
 
 
-def test_eviction_step_overwrites_or_extends_per_head(kb):
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+def test_eviction_step_overwrites_or_extends_per_head(kb, dtype):
     """One decode step of a token-dropping policy: the new token of each kv head either replaces
     the token that head evicts or extends the head's list; then attention over the new sets."""
     L, Hq, Hkv, d, B, cap, T = 2, 8, 4, 128, 2, 96, 80
     share = np.array([0, 0], np.int32)
-    case = Case(kb, L, Hq, Hkv, d, B, "bf16", cap, share, paged=True, seed=33, fill_tokens=T)
+    case = Case(kb, L, Hq, Hkv, d, B, dtype, cap, share, paged=True, seed=33, fill_tokens=T)
     rng = np.random.default_rng(33)
     keep = _keep_lists(rng, B, Hkv, [T] * B, 0.4, 0.8)
     idx, cnt = _pack(keep, B, Hkv)
@@ -130,8 +131,9 @@ def test_eviction_step_overwrites_or_extends_per_head(kb):
             else:                                             # nothing evicted: the list grows
                 pos[b, h] = counts[b, h]
                 lens[b, h] += 1
-            Kc[b, pos[b, h], h] = inputs.to_oracle_array(k_new)[b, 0, h]
-            Vc[b, pos[b, h], h] = inputs.to_oracle_array(v_new)[b, 0, h]
+            kn, vn = inputs.to_oracle_array(k_new)[b, 0, h], inputs.to_oracle_array(v_new)[b, 0, h]
+            Kc[b, pos[b, h], h] = stored_fp8(kn) if dtype == "fp8" else kn
+            Vc[b, pos[b, h], h] = stored_fp8(vn) if dtype == "fp8" else vn
     assert kb.kvs_append_kv_per_head(case.store, 1, k_new.cuda(), v_new.cuda(), pos) == kb.KVS_NOOP
     assert kb.kvs_append_kv_per_head(case.store, 0, k_new.cuda(), v_new.cuda(), pos) == kb.KVS_OK
     k, v = kb.kvs_gather_kv(case.store, 1, 0, cap, B)
