@@ -81,7 +81,8 @@ def bench_prefill(args, torch, kb, inputs, dev):
         sys.exit(f"--prefill-rows must be in [1, {w.context}]")
     mb = w.max_blocks_per_seq
     table = inputs.make_block_table(w.B, mb, w.B * mb, 1)
-    store = kb.KVStore(np.arange(n_layers, dtype=np.int32), w.Hq, w.Hkv, w.d, "bf16", w.B * mb, mb, block_table=table)
+    store_dtype = args.store or "bf16"                        # --store fp8: the same rows in 8-bit slots
+    store = kb.KVStore(np.arange(n_layers, dtype=np.int32), w.Hq, w.Hkv, w.d, store_dtype, w.B * mb, mb, block_table=table)
     gen = torch.Generator(device=dev)
     gen.manual_seed(inputs.SEED_BASE)
     zeros = torch.zeros(w.B, dtype=torch.int32, device=dev)
@@ -106,7 +107,7 @@ def bench_prefill(args, torch, kb, inputs, dev):
 
     attn_us = _event_time_us(torch, attn, args.steps, args.warmup)
     append_us = _event_time_us(torch, append, args.steps, args.warmup)
-    kv_bytes = w.B * w.context * w.Hkv * w.d * 2 * 2 + w.B * T * w.Hq * w.d * (2 + 4)
+    kv_bytes = w.B * w.context * w.Hkv * w.d * 2 * (1 if store_dtype == "fp8" else 2) + w.B * T * w.Hq * w.d * (2 + 4)
     # row i of the chunk sees prefix + i + 1 keys; 2 flops per multiply-add, scores and values
     keys_seen = T * (w.context - T) + T * (T + 1) // 2
     flops = 4.0 * w.B * w.Hq * w.d * keys_seen
@@ -131,7 +132,7 @@ def bench_prefill(args, torch, kb, inputs, dev):
         "metric": "causal prefill chunk attention, rows/s", "value": round(w.B * T / (attn_us * 1e-6), 1),
         "unit": "query rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(attn_us * 1e-3, 4), "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "llama2-13b prefill chunk", "batch": w.B, "rows": T, "prefix": w.context - T,
+        "config": {"workload": "llama2-13b prefill chunk" + (", fp8 slots" if store_dtype == "fp8" else ""), "batch": w.B, "rows": T, "prefix": w.context - T,
                    "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d},
         "append_us": round(append_us, 2),
         "roofline": roof}))
