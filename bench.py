@@ -304,7 +304,7 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="decode mode: record the step's launches once into a HIP graph and time its replays")
     ap.add_argument("--store", choices=["fp8"], default=None,
-                    help="decode mode: keep the slots in fp8 (E4M3) instead of the workload's type")
+                    help="decode and prefill modes: keep the slots in fp8 (E4M3) instead of the workload's type")
     ap.add_argument("--prefill-rows", type=int, default=0,
                     help="--mode prefill: rows per sequence in the chunk (default: the workload's 64)")
     ap.add_argument("--project-rows", type=int, default=1,
