@@ -777,6 +777,10 @@ void attn_bf16_wide_kernel(AttnArgs a)
     const int wg_pages = (n0 + wg_hi / group + kPageTokens - 1) / kPageTokens;
     const int wg_pairs = (wg_pages + 1) / 2;
 
+    // The small bf16 variant takes its pages from global memory straight into LDS (the plain page
+    // image is exactly what a wavefront-wide 16-byte-per-lane load lays down): no staging registers,
+    // no LDS store instructions.
+    constexpr bool kDma = NT == 1 && !kFp8;
     __shared__ u32x4 tile[2][2 * kPageVecs];
     using Elem = std::conditional_t<kFp8, unsigned char, unsigned short>;   // page_offset counts elements
     const Elem* pool = static_cast<const Elem*>(st.pool);
@@ -849,9 +853,8 @@ void attn_bf16_wide_kernel(AttnArgs a)
     // j & 1), then pair + 1 goes from its register slot into the other buffer and pair + 1 + kDepth
     // is fetched into that slot.  kAll: every fetch, LDS write and barrier is known to be due, and
     // the step is straight-line code.
-#define KVS_WIDE_STEP(pair, j, kAll)                                                                  \
-    if (kAll || (pair) < wg_pairs) {                                                                  \
-        const int buf = (j) & 1;                                   /* kDepth is even */               \
+#define KVS_WIDE_COMPUTE(pair, buf)                                                                   \
+    {                                                                                                 \
         const int tok_a = 2 * (pair) * kPageTokens, tok_b = tok_a + kPageTokens;                      \
         if (tok_a < n_max) {                                                                          \
             const bool have_b = 2 * (pair) + 1 < my_pages;                                            \
@@ -881,6 +884,11 @@ void attn_bf16_wide_kernel(AttnArgs a)
                 pair_values<D, NT>(va, vb, have_b, tok_a, tok_b, n_max, quad, pf, o);                 \
             }                                                                                         \
         }                                                                                             \
+    }
+#define KVS_WIDE_STEP(pair, j, kAll)                                                                  \
+    if (kAll || (pair) < wg_pairs) {                                                                  \
+        const int buf = (j) & 1;                                   /* kDepth is even */               \
+        KVS_WIDE_COMPUTE(pair, buf)                                                                   \
         if (kAll || (pair) + 1 < wg_pairs) {                                                          \
             KVS_PUT_PAIR(buf ^ 1, ((j) + 1) % kDepth)              /* that buffer was last read before the previous barrier */ \
             if (kAll || (pair) + 1 + kDepth < wg_pairs) { KVS_FETCH_PAIR((pair) + 1 + kDepth, ((j) + 1) % kDepth) } \
@@ -896,6 +904,55 @@ void attn_bf16_wide_kernel(AttnArgs a)
     // pairs take the same step with its branches.
     // (Only in the 8-wavefront variant: the small one, bound by HBM and not by its own latencies,
     // measured 128 us with exact waits against 122 us with the draining ones on the 64-row chunk.)
+    if constexpr (kDma) {
+        static_assert(!kDma || kPageVecs % kWideThreads == 0, "whole passes of the workgroup over a page");
+        // Direct loads: pair p lives in buffer p % 2.  At step i the loads of pair i + 1 are issued
+        // into the buffer pair i - 1 was read from (all wavefronts have passed the barrier behind it),
+        // pair i is consumed, and before the barrier every wavefront waits until its loads have
+        // landed.  One pair of look-ahead is the measured optimum on the 64-row chunk of the
+        // Llama-2-13B shape: two pairs ahead with exact waits took 128 us against 115 us (640
+        // workgroups already keep 10 MB in flight; more only lengthens the queues of the memory).
+        // The loads are assembly (the compiler would otherwise hold every LDS read behind them) and
+        // so are the waits.
+#define KVS_DMA_PAIR(pair, buf)                                                                       \
+        _Pragma("unroll") for (int pg = 0; pg < 2; ++pg) {                                            \
+            int page = 2 * (pair) + pg;                                                               \
+            page = page < wg_pages ? page : (wg_pages > 0 ? wg_pages - 1 : 0);                        \
+            const u32x4* src = reinterpret_cast<const u32x4*>(pool + page_offset(st, slot, safe_block_of_uniform(st, b, page), g)); \
+            _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                     \
+                const unsigned to = (unsigned)(size_t)&tile[buf][pg * kPageVecs + i * kWideThreads + wave * 64]; \
+                if constexpr (kReadOnce)                                                              \
+                    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" \
+                                 :: "v"(src + i * kWideThreads + (int)threadIdx.x), "s"(to) : "memory"); \
+                else                                                                                  \
+                    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"  \
+                                 :: "v"(src + i * kWideThreads + (int)threadIdx.x), "s"(to) : "memory"); \
+            }                                                                                         \
+        }
+#define KVS_WAIT_LANDED asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[ct][ks]));   // the queries have arrived
+        if (wg_pairs > 0) { KVS_DMA_PAIR(0, 0) }
+        KVS_WAIT_LANDED
+        __builtin_amdgcn_s_barrier();
+        for (int p0 = 0; p0 < wg_pairs; p0 += 2) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int pair = p0 + j;
+                if (pair < wg_pairs) {                                 // uniform over the workgroup
+                    if (pair + 1 < wg_pairs) { KVS_DMA_PAIR(pair + 1, j ^ 1) }
+                    KVS_WIDE_COMPUTE(pair, j)
+                    KVS_WAIT_LANDED
+                    __builtin_amdgcn_s_barrier();
+                }
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef KVS_WAIT_LANDED
+#undef KVS_DMA_PAIR
+    } else {
     const int n_straight = NT > 1 && wg_pairs > kDepth + 1 ? (wg_pairs - kDepth - 1) / kDepth * kDepth : 0;
     if (n_straight > 0) {
 #pragma unroll
@@ -925,7 +982,9 @@ void attn_bf16_wide_kernel(AttnArgs a)
 #pragma unroll
         for (int j = 0; j < kDepth; ++j) { KVS_WIDE_STEP(p0 + j, j, false) }
     }
+    }
 #undef KVS_WIDE_STEP
+#undef KVS_WIDE_COMPUTE
 #undef KVS_FETCH_PAIR
 #undef KVS_PUT_PAIR
 #undef KVS_STORE_PIECE
