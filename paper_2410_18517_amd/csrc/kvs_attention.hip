@@ -715,7 +715,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 // registers in flight) and widened to bf16 once, by the thread that lays it into LDS; LDS holds the
 // bf16 page and everything downstream is the same code.
 template <int D, int NT, int WAVES, bool kReadOnce, bool kFp8>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3 : 2)))
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(NT == 1 ? (kFp8 ? 3 : 4) : 2)))
 void attn_bf16_wide_kernel(AttnArgs a)
 {
     constexpr int KS = D / 32, DT = D / 16;
