@@ -115,9 +115,11 @@ def bench_prefill(args, torch, kb, inputs, dev):
     group = w.Hq // w.Hkv
     ncols = T * group
     if ncols >= 256 and w.Hkv * w.B * ((ncols + 255) // 256) >= 256:
-        kernel = "attn_bf16_wide_kernel<128,2,8,%s>" % ("true" if ncols <= 256 else "false")    # pages read once?
+        kernel = "attn_bf16_wide_kernel<128,2,8,%s,%s>" % ("true" if ncols <= 256 else "false",    # pages read once? fp8 slots?
+                                                           "true" if store_dtype == "fp8" else "false")
     elif ncols >= 64 and w.Hkv * w.B * ((ncols + 63) // 64) >= 512:
-        kernel = "attn_bf16_wide_kernel<128,1,4,%s>" % ("true" if ncols <= 64 else "false")
+        kernel = "attn_bf16_wide_kernel<128,1,4,%s,%s>" % ("true" if ncols <= 64 else "false",
+                                                           "true" if store_dtype == "fp8" else "false")
     else:
         kernel = "attn_bf16_kernel<128,4,2>"
     if T < 512:
