@@ -221,6 +221,27 @@ def test_shared_page_prefill_kernels(kb, d, Hq, Hkv, B, T_new):
     assert rel_l2_rows(short, got[:, -tail:].astype(np.float64)).max() <= REL_L2_ATTENTION
 
 
+# Column counts on either side of the limits at which the prefill kernels change hands (64 and 256
+# columns per (sequence, kv head)), with enough workgroups for the shared-page kernels to be chosen:
+# a last column block of a single column leaves wavefronts without any column.
+@pytest.mark.parametrize("Hq,Hkv,B,T_new", [(8, 8, 64, 63), (8, 8, 64, 64), (8, 8, 64, 65),
+                                            (16, 8, 32, 127), (16, 8, 32, 128), (16, 8, 32, 129)])
+def test_prefill_kernel_boundaries(kb, Hq, Hkv, B, T_new):
+    d, cap = 128, 208
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, 2, Hq, Hkv, d, B, "bf16", cap, share, paged=True, seed=57)
+    rng = np.random.default_rng(57)
+    start = rng.integers(0, cap - T_new + 1, size=B).astype(np.int32)
+    start[0], start[-1] = 0, cap - T_new
+    q = case.q(1, rows=T_new)
+    got = kb.kvs_prefill_attention(case.store, 1, q.cuda(), start).cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in (0, B // 3, B - 1):
+        want = orc.shared_attention(1, share, [case.K[0][b:b + 1], None], [case.V[0][b:b + 1], None],
+                                    inputs.to_oracle_array(q[b:b + 1]), start[b:b + 1])
+        assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, b
+
+
 @pytest.mark.parametrize("Hq,Hkv,B,T_new", [(16, 8, 16, 160),      # 320 columns: the 8-wavefront shared-page kernel
                                             (8, 8, 64, 80)])       # 80 columns: the 4-wavefront one
 def test_shared_page_prefill_rising_scores(kb, Hq, Hkv, B, T_new):
