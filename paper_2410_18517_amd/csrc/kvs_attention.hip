@@ -780,7 +780,7 @@ void attn_bf16_wide_kernel(AttnArgs a)
     // The small bf16 variant takes its pages from global memory straight into LDS (the plain page
     // image is exactly what a wavefront-wide 16-byte-per-lane load lays down): no staging registers,
     // no LDS store instructions.
-    constexpr bool kDma = NT == 1 && !kFp8;
+    constexpr bool kDma = NT == 1 && !kFp8 && kPageVecs % kWideThreads == 0;
     __shared__ u32x4 tile[2][2 * kPageVecs];
     using Elem = std::conditional_t<kFp8, unsigned char, unsigned short>;   // page_offset counts elements
     const Elem* pool = static_cast<const Elem*>(st.pool);
@@ -1017,6 +1017,14 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
             hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, true, kFp8>), grid, dim3(512), 0, s, a);
         else
             hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, false, kFp8>), grid, dim3(512), 0, s, a);
+    } else if (ncols > 64 && (long)a.st.Hkv * a.B * ((ncols + 127) / 128) >= 512) {
+        // Between 65 and 255 columns: eight wavefronts of 16 columns, so that 128 columns share one
+        // pass over the pages.
+        dim3 grid(a.st.Hkv, a.B, (ncols + 127) / 128);
+        if (grid.z == 1)
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 8, true, kFp8>), grid, dim3(512), 0, s, a);
+        else
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 8, false, kFp8>), grid, dim3(512), 0, s, a);
     } else if (ncols >= 64 && (long)a.st.Hkv * a.B * ((ncols + 63) / 64) >= 512) {
         // Fewer columns: 16 per wavefront, four wavefronts; small enough in registers for several
         // workgroups per compute unit to hide each other's softmax arithmetic.

@@ -194,7 +194,8 @@ def test_causal_prefill(kb, dtype, Hq, Hkv, d, T_new):
 # Shapes that reach each instantiation of the shared-page prefill kernel (a workgroup's wavefronts
 # take separate columns and read every page pair from LDS): it is used when one (sequence, kv
 # head) has at least 256 query columns (rows x group size) and there are at least 256 such
-# workgroups, or at least 64 columns and 512 workgroups.  Ragged column counts, a group size of two,
+# workgroups, or 65 to 255 columns and 512 workgroups of 128 columns, or at least 64 columns and
+# 512 workgroups of 64 (test_prefill_kernel_boundaries walks the limits).  Ragged column counts, a group size of two,
 # different start positions per sequence, a permuted page table, a recipient layer.
 @pytest.mark.parametrize("d,Hq,Hkv,B,T_new", [(128, 16, 8, 16, 150),     # 300 columns -> 2 x 256-column workgroups, 8 wavefronts
                                               (128, 16, 8, 16, 100),     # 200 columns -> 4 x 64-column workgroups, 4 wavefronts
