@@ -114,7 +114,7 @@ def bench_prefill(args, torch, kb, inputs, dev):
     # which prefill kernel the library's launch rule picks for this shape
     group = w.Hq // w.Hkv
     ncols = T * group
-    if ncols >= 256 and w.Hkv * w.B * ((ncols + 255) // 256) >= 256:
+    if ncols > 128 and w.Hkv * w.B * ((ncols + 255) // 256) >= 256:
         kernel = "attn_bf16_wide_kernel<128,2,8,%s,%s>" % ("true" if ncols <= 256 else "false",    # pages read once? fp8 slots?
                                                            "true" if store_dtype == "fp8" else "false")
     elif ncols > 64 and w.Hkv * w.B * ((ncols + 127) // 128) >= 512:

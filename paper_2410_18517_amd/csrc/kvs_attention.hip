@@ -1009,7 +1009,7 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
     if (a.T_new == 1) {
         dim3 grid(a.st.Hkv, a.B, a.n_splits);
         hipLaunchKernelGGL((attn_bf16_kernel<D, 1, 4, kFp8>), grid, dim3(kThreads), 0, s, a);
-    } else if (const int ncols = a.T_new * group; ncols >= 256 && (long)a.st.Hkv * a.B * ((ncols + 255) / 256) >= 256) {
+    } else if (const int ncols = a.T_new * group; ncols > 128 && (long)a.st.Hkv * a.B * ((ncols + 255) / 256) >= 256) {
         // Enough columns per (sequence, kv head) to share every page among eight wavefronts, and
         // enough such workgroups to cover the chip without splitting the context.
         dim3 grid(a.st.Hkv, a.B, (ncols + 255) / 256);
