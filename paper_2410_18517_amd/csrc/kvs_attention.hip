@@ -226,6 +226,64 @@ __device__ __forceinline__ floatx2 fetch_pair(const float* p)
     return __builtin_bit_cast(floatx2, w);
 }
 
+// The end of a workgroup that has published its partial states: the one that arrives last at
+// its (sequence, kv head, column group) merges the splits.  Nobody waits: each workgroup publishes
+// its partial state, bumps the counter and leaves; the one that reads (live splits - 1) finds every
+// other state already published.  Returns whether this workgroup is that last one.
+__device__ __forceinline__ bool arrived_last(int* counter, int live_splits)
+{
+    __shared__ int s_is_last;
+    // vmcnt(0): every device-scope store this wavefront issued has been acknowledged.  A
+    // workgroup-scope fence would not wait for that (the compute unit orders its own accesses).
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int arrived = atomicAdd(counter, 1);
+        s_is_last = arrived == live_splits - 1;
+        if (s_is_last) atomicExch(counter, 0);          // leave the counter ready for the next call
+    }
+    __syncthreads();
+    if (!s_is_last) return false;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    return true;
+}
+
+// Merge of the published states of `live_splits` splits for the columns [first_col, first_col +
+// n_cols) of (sequence b, kv head g): the normalised output rows.
+template <int D>
+__device__ __forceinline__ void merge_splits(const AttnArgs& a, int b, int g, int first_col, int n_cols, int ncols,
+                                             int group, int live_splits, int n_threads)
+{
+    const StoreView& st = a.st;
+    for (int idx = threadIdx.x; idx < n_cols * (D / 4); idx += n_threads) {
+        const int cidx = first_col + idx / (D / 4);
+        const int d4 = (idx % (D / 4)) * 4;
+        if (cidx >= ncols) break;
+        const int r = cidx / group, hc = cidx % group;
+        const size_t row = ((size_t)b * a.T_new + r) * st.Hq + g * group + hc;
+        const float* part = a.partials + row * a.n_splits * (size_t)(D + 2);
+        float M = -INFINITY;
+#pragma unroll 8
+        for (int s = 0; s < live_splits; ++s) M = fmaxf(M, fetch_pair(part + s * (D + 2) + D)[0]);
+        const float M_use = M == -INFINITY ? 0.f : M;
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        float lt = 0.f;
+#pragma unroll 4
+        for (int s = 0; s < live_splits; ++s) {
+            const float* ps = part + s * (D + 2);
+            const floatx2 ml = fetch_pair(ps + D);
+            const floatx2 lo = fetch_pair(ps + d4);
+            const floatx2 hi = fetch_pair(ps + d4 + 2);
+            const float wgt = __builtin_amdgcn_exp2f(ml[0] - M_use);   // empty splits carry m = -inf
+            acc += wgt * floatx4{lo[0], lo[1], hi[0], hi[1]};
+            lt += wgt * ml[1];
+        }
+        const float inv = lt > 0.f ? 1.f / lt : 0.f;
+        *reinterpret_cast<floatx4*>(a.out + row * D + d4) = acc * inv;
+    }
+}
+
 // Reductions over the four lanes l, l^16, l^32, l^48 that hold one query column, with the
 // gfx950 lane-swap instructions: permlane16_swap(x, x) returns the pair (rows 0,0,2,2 of x,
 // rows 1,1,3,3 of x) for 16-lane rows, permlane32_swap the same for 32-lane halves, so two
@@ -644,52 +702,9 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     }
     if (live_splits <= 1) return;
 
-    // The workgroup that arrives last at this (sequence, kv head, column group) merges the
-    // splits.  Nobody waits: each workgroup publishes its partial state, bumps the counter
-    // and leaves; the one that reads (live splits - 1) finds every other state already published.
-    __shared__ int s_is_last;
-    // vmcnt(0): every device-scope store this wavefront issued has been acknowledged.  A
-    // workgroup-scope fence would not wait for that (the compute unit orders its own accesses).
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const int n_col_groups = gridDim.z / a.n_splits;
-        int* counter = a.counters + ((size_t)b * st.Hkv + g) * n_col_groups + cgrp;
-        const int arrived = atomicAdd(counter, 1);
-        s_is_last = arrived == live_splits - 1;
-        if (s_is_last) atomicExch(counter, 0);          // leave the counter ready for the next call
-    }
-    __syncthreads();
-    if (!s_is_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const int wg_cols = NT * 16;
-    for (int idx = threadIdx.x; idx < wg_cols * (D / 4); idx += kThreads) {
-        const int cidx = cgrp * wg_cols + idx / (D / 4);
-        const int d4 = (idx % (D / 4)) * 4;
-        if (cidx >= ncols) break;
-        const int r = cidx / group, hc = cidx % group;
-        const size_t row = ((size_t)b * a.T_new + r) * st.Hq + g * group + hc;
-        const float* part = a.partials + row * a.n_splits * (size_t)(D + 2);
-        float M = -INFINITY;
-#pragma unroll 8
-        for (int s = 0; s < live_splits; ++s) M = fmaxf(M, fetch_pair(part + s * (D + 2) + D)[0]);
-        const float M_use = M == -INFINITY ? 0.f : M;
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        float lt = 0.f;
-#pragma unroll 4
-        for (int s = 0; s < live_splits; ++s) {
-            const float* ps = part + s * (D + 2);
-            const floatx2 ml = fetch_pair(ps + D);
-            const floatx2 lo = fetch_pair(ps + d4);
-            const floatx2 hi = fetch_pair(ps + d4 + 2);
-            const float wgt = __builtin_amdgcn_exp2f(ml[0] - M_use);   // empty splits carry m = -inf
-            acc += wgt * floatx4{lo[0], lo[1], hi[0], hi[1]};
-            lt += wgt * ml[1];
-        }
-        const float inv = lt > 0.f ? 1.f / lt : 0.f;
-        *reinterpret_cast<floatx4*>(a.out + row * D + d4) = acc * inv;
-    }
+    const int n_col_groups = gridDim.z / a.n_splits;
+    if (!arrived_last(a.counters + ((size_t)b * st.Hkv + g) * n_col_groups + cgrp, live_splits)) return;
+    merge_splits<D>(a, b, g, cgrp * NT * 16, NT * 16, ncols, group, live_splits, kThreads);
 }
 
 // ------------------------------------------------------------------ wide prefill
