@@ -114,15 +114,13 @@ def bench_prefill(args, torch, kb, inputs, dev):
     # which prefill kernel the library's launch rule picks for this shape
     group = w.Hq // w.Hkv
     ncols = T * group
-    if ncols > 128 and w.Hkv * w.B * ((ncols + 255) // 256) >= 256:
-        kernel = "attn_bf16_wide_kernel<128,2,8,%s,%s>" % ("true" if ncols <= 256 else "false",    # pages read once? fp8 slots?
-                                                           "true" if store_dtype == "fp8" else "false")
-    elif ncols > 64 and w.Hkv * w.B * ((ncols + 127) // 128) >= 512:
-        kernel = "attn_bf16_wide_kernel<128,1,8,%s,%s>" % ("true" if ncols <= 128 else "false",
-                                                           "true" if store_dtype == "fp8" else "false")
-    elif ncols >= 64 and w.Hkv * w.B * ((ncols + 63) // 64) >= 512:
-        kernel = "attn_bf16_wide_kernel<128,1,4,%s,%s>" % ("true" if ncols <= 64 else "false",
-                                                           "true" if store_dtype == "fp8" else "false")
+    fp8 = "true" if store_dtype == "fp8" else "false"
+    if ncols > 128:
+        kernel = "attn_bf16_wide_kernel<128,2,8,%s,%s>" % ("true" if ncols <= 256 else "false", fp8)   # pages read once?
+    elif ncols > 64:
+        kernel = "attn_bf16_wide_kernel<128,1,8,true,%s>" % fp8
+    elif ncols == 64:
+        kernel = "attn_bf16_wide_kernel<128,1,4,true,%s>" % fp8
     else:
         kernel = "attn_bf16_kernel<128,4,2>"
     if T < 512:

@@ -718,9 +718,12 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 // operand order, so a lane's operand is the 16 bytes at its own index); values the same in the
 // small variant, and in the large one with the two pages' halves interleaved, so that a lane reads
 // the eight-token operand of the value product in one piece.  Each wavefront reads them back after
-// a barrier.  A wavefront owns its columns for the whole context: no state is merged, no splits,
-// the output is written normalised.  Causality: a wavefront skips the pairs that lie beyond the
-// last key any of its columns sees.
+// a barrier.  A wavefront owns its columns for all the pairs of its workgroup: no state is merged
+// inside a workgroup.  grid.z = column blocks x context splits: with one split the output is
+// written normalised; with several (few sequences x heads, long context: the host splits the pairs
+// over workgroups to fill the chip) every workgroup publishes its columns' states and the last to
+// arrive merges them.  Causality: a wavefront skips the pairs that lie beyond the last key any of
+// its columns sees.
 // NT 16-column tiles per wavefront, WAVES wavefronts: NT * 16 * WAVES columns per workgroup.
 // kReadOnce: one column block per (sequence, kv head), so that every page is read exactly once per
 // launch and is streamed past the caches (nontemporal loads); with several blocks the later ones
@@ -747,7 +750,11 @@ void attn_bf16_wide_kernel(AttnArgs a)
     const int quad = lane >> 4, col = lane & 15;
     // later column blocks see more keys (causality) and run longer: they are started first, so
     // that the launch does not end on its longest workgroups
-    const int g = blockIdx.x, b = blockIdx.y, cblk = gridDim.z - 1 - blockIdx.z;
+    // grid.z = column blocks x context splits, the split index fastest
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int n_cblk = gridDim.z / a.n_splits;
+    const int split = (int)blockIdx.z % a.n_splits;
+    const int cblk = n_cblk - 1 - (int)blockIdx.z / a.n_splits;
     const int group = st.Hq / st.Hkv;
     const int ncols = a.T_new * group;
     const int cap = st.max_blocks_per_seq * kPageTokens;
@@ -790,7 +797,16 @@ void attn_bf16_wide_kernel(AttnArgs a)
     int wg_hi = cblk * kWideCols + kWideCols - 1;
     if (wg_hi > ncols - 1) wg_hi = ncols - 1;
     const int wg_pages = (n0 + wg_hi / group + kPageTokens - 1) / kPageTokens;
-    const int wg_pairs = (wg_pages + 1) / 2;
+    // With few (sequence, kv head) pairs and a long context the pairs of pages are also split
+    // over workgroups (a.pages_per_split is a multiple of four): this one takes pairs pair_lo ..
+    // pair_lo + wg_pairs, and where more than one split has work the states are published and merged
+    // by the last to arrive, as in the kernel above.
+    const int all_pairs = (wg_pages + 1) / 2;
+    const int pairs_per_split = a.pages_per_split / 2;
+    const int live_splits = (all_pairs + pairs_per_split - 1) / pairs_per_split;
+    if (split > 0 && split >= live_splits) return;
+    const int pair_lo = split * pairs_per_split;
+    const int wg_pairs = all_pairs - pair_lo < pairs_per_split ? (all_pairs > pair_lo ? all_pairs - pair_lo : 0) : pairs_per_split;
 
     // The small bf16 variant takes its pages from global memory straight into LDS (the plain page
     // image is exactly what a wavefront-wide 16-byte-per-lane load lays down): no staging registers,
@@ -810,7 +826,7 @@ void attn_bf16_wide_kernel(AttnArgs a)
     // which does not queue behind the vector loads already in flight.
 #define KVS_FETCH_PAIR(pair, slot_)                                                                   \
     _Pragma("unroll") for (int pg = 0; pg < 2; ++pg) {                                                \
-        int page = 2 * (pair) + pg;                                                                   \
+        int page = 2 * (pair_lo + (pair)) + pg;                                                       \
         page = page < wg_pages ? page : (wg_pages > 0 ? wg_pages - 1 : 0);   /* past the end: a page nobody reads */ \
         const u32x4* src = reinterpret_cast<const u32x4*>(pool + page_offset(st, slot, safe_block_of_uniform(st, b, page), g)); \
         _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                         \
@@ -870,9 +886,9 @@ void attn_bf16_wide_kernel(AttnArgs a)
     // the step is straight-line code.
 #define KVS_WIDE_COMPUTE(pair, buf)                                                                   \
     {                                                                                                 \
-        const int tok_a = 2 * (pair) * kPageTokens, tok_b = tok_a + kPageTokens;                      \
+        const int tok_a = 2 * (pair_lo + (pair)) * kPageTokens, tok_b = tok_a + kPageTokens;          \
         if (tok_a < n_max) {                                                                          \
-            const bool have_b = 2 * (pair) + 1 < my_pages;                                            \
+            const bool have_b = 2 * (pair_lo + (pair)) + 1 < my_pages;                                \
             /* keys first; the value operands are fetched from LDS once the score products are */     \
             /* issued, into the registers the keys no longer need */                                  \
             constexpr int kSecond = kCatV ? KS * 64 : kPageVecs;   /* where the second page's keys start */ \
@@ -931,7 +947,7 @@ void attn_bf16_wide_kernel(AttnArgs a)
         // so are the waits.
 #define KVS_DMA_PAIR(pair, buf)                                                                       \
         _Pragma("unroll") for (int pg = 0; pg < 2; ++pg) {                                            \
-            int page = 2 * (pair) + pg;                                                               \
+            int page = 2 * (pair_lo + (pair)) + pg;                                                   \
             page = page < wg_pages ? page : (wg_pages > 0 ? wg_pages - 1 : 0);                        \
             const u32x4* src = reinterpret_cast<const u32x4*>(pool + page_offset(st, slot, safe_block_of_uniform(st, b, page), g)); \
             _Pragma("unroll") for (int i = 0; i < kPasses; ++i) {                                     \
@@ -1009,12 +1025,26 @@ void attn_bf16_wide_kernel(AttnArgs a)
     for (int ct = 0; ct < NT; ++ct) {
         const float lsum = column_sum(l[ct]);
         if (!col_ok[ct]) continue;
-        const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
         const int cidx = c_lo + ct * 16 + col;
-        float* dst = a.out + (((size_t)b * a.T_new + cidx / group) * st.Hq + g * group + cidx % group) * D + quad * 4;
+        const size_t row = ((size_t)b * a.T_new + cidx / group) * st.Hq + g * group + cidx % group;
+        if (live_splits <= 1) {                                    // the only split with keys: the finished rows
+            const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+            float* dst = a.out + row * D + quad * 4;
 #pragma unroll
-        for (int c = 0; c < DT; ++c) *reinterpret_cast<floatx4*>(dst + c * 16) = o[ct][c] * inv;
+            for (int c = 0; c < DT; ++c) *reinterpret_cast<floatx4*>(dst + c * 16) = o[ct][c] * inv;
+        } else {                                                   // this split's state of the column
+            float* part = a.partials + (row * a.n_splits + split) * (size_t)(D + 2);
+#pragma unroll
+            for (int c = 0; c < DT; ++c) {
+                publish_pair(part + c * 16 + quad * 4, o[ct][c][0], o[ct][c][1]);
+                publish_pair(part + c * 16 + quad * 4 + 2, o[ct][c][2], o[ct][c][3]);
+            }
+            if (quad == 0) publish_pair(part + D, m[ct], lsum);
+        }
     }
+    if (live_splits <= 1) return;
+    if (!arrived_last(a.counters + ((size_t)b * st.Hkv + g) * n_cblk + cblk, live_splits)) return;
+    merge_splits<D>(a, b, g, cblk * kWideCols, kWideCols, ncols, group, live_splits, kWideThreads);
 }
 
 template <int D, bool kFp8>
@@ -1024,30 +1054,26 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
     if (a.T_new == 1) {
         dim3 grid(a.st.Hkv, a.B, a.n_splits);
         hipLaunchKernelGGL((attn_bf16_kernel<D, 1, 4, kFp8>), grid, dim3(kThreads), 0, s, a);
-    } else if (const int ncols = a.T_new * group; ncols > 128 && (long)a.st.Hkv * a.B * ((ncols + 255) / 256) >= 256) {
-        // Enough columns per (sequence, kv head) to share every page among eight wavefronts, and
-        // enough such workgroups to cover the chip without splitting the context.
-        dim3 grid(a.st.Hkv, a.B, (ncols + 255) / 256);
-        if (grid.z == 1)
+    } else if (a.wide_cols == 256) {
+        // Shared-page kernels (the host chose the shape by the number of columns per (sequence, kv
+        // head) and, where those workgroups alone would not fill the chip, a split of the context).
+        // Enough columns to share every page among eight wavefronts of 32 columns:
+        const int ncols = a.T_new * group;
+        const unsigned blocks = (ncols + 255) / 256;
+        dim3 grid(a.st.Hkv, a.B, blocks * a.n_splits);
+        if (blocks == 1)
             hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, true, kFp8>), grid, dim3(512), 0, s, a);
         else
             hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, false, kFp8>), grid, dim3(512), 0, s, a);
-    } else if (ncols > 64 && (long)a.st.Hkv * a.B * ((ncols + 127) / 128) >= 512) {
-        // Between 65 and 255 columns: eight wavefronts of 16 columns, so that 128 columns share one
-        // pass over the pages.
-        dim3 grid(a.st.Hkv, a.B, (ncols + 127) / 128);
-        if (grid.z == 1)
-            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 8, true, kFp8>), grid, dim3(512), 0, s, a);
-        else
-            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 8, false, kFp8>), grid, dim3(512), 0, s, a);
-    } else if (ncols >= 64 && (long)a.st.Hkv * a.B * ((ncols + 63) / 64) >= 512) {
-        // Fewer columns: 16 per wavefront, four wavefronts; small enough in registers for several
+    } else if (a.wide_cols == 128) {
+        // 65 to 128 columns: eight wavefronts of 16 columns, so that 128 columns share one pass over the pages.
+        dim3 grid(a.st.Hkv, a.B, a.n_splits);
+        hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 8, true, kFp8>), grid, dim3(512), 0, s, a);
+    } else if (a.wide_cols == 64) {
+        // 64 columns: 16 per wavefront, four wavefronts; small enough in registers for several
         // workgroups per compute unit to hide each other's softmax arithmetic.
-        dim3 grid(a.st.Hkv, a.B, (ncols + 63) / 64);
-        if (grid.z == 1)
-            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4, true, kFp8>), grid, dim3(256), 0, s, a);
-        else
-            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4, false, kFp8>), grid, dim3(256), 0, s, a);
+        dim3 grid(a.st.Hkv, a.B, a.n_splits);
+        hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 1, 4, true, kFp8>), grid, dim3(256), 0, s, a);
     } else {
         const int cgroups = (a.T_new * group + 63) / 64;
         dim3 grid(a.st.Hkv, a.B, a.n_splits * cgroups);

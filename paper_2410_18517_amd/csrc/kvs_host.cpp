@@ -128,12 +128,13 @@ kvs::StoreView view_of(const kvs_store* s, int layer)
 // Query columns (row, head-in-group pairs) one workgroup of the bf16 kernel covers.
 int columns_per_workgroup(int T_new) { return T_new > 1 ? 64 : 16; }
 
-struct Split { int pages_per_split, n_splits, n_col_groups; };
+struct Split { int pages_per_split, n_splits, n_col_groups, wide_cols; };
 
 Split choose_split(const kvs_desc* d, int B, int T_new)
 {
     Split s;
     const int max_pages = d->max_blocks_per_seq;
+    s.wide_cols = 0;
     if (d->dtype == KVS_F32) {           // the fp32 kernel walks the whole context in one wave
         s.pages_per_split = max_pages;
         s.n_splits = 1;
@@ -141,14 +142,23 @@ Split choose_split(const kvs_desc* d, int B, int T_new)
         return s;
     }
     const int group = d->Hq / d->Hkv;
-    s.n_col_groups = (T_new * group + columns_per_workgroup(T_new) - 1) / columns_per_workgroup(T_new);
+    const int ncols = T_new * group;
+    s.n_col_groups = (ncols + columns_per_workgroup(T_new) - 1) / columns_per_workgroup(T_new);
+    // Prefill with at least 64 query columns per (sequence, kv head) takes a shared-page kernel: 256
+    // columns per workgroup (8 wavefronts x 32), 128 (8 x 16) or 64 (4 x 16).  The smaller two run
+    // several workgroups per compute unit, hence the larger target.
+    long items = (long)B * d->Hkv * s.n_col_groups, target = kTargetWorkgroups;
+    if (T_new > 1 && ncols >= 64) {
+        s.wide_cols = ncols > 128 ? 256 : (ncols > 64 ? 128 : 64);
+        items = (long)B * d->Hkv * ((ncols + s.wide_cols - 1) / s.wide_cols);
+        target = s.wide_cols == 256 ? kTargetWorkgroups : 2 * kTargetWorkgroups;
+    }
     int pps;
     const int forced = g_split_tokens.load();
     if (forced > 0) {
         pps = forced / KVS_BLOCK_TOKENS;
     } else {
-        const long items = (long)B * d->Hkv * s.n_col_groups;
-        long want = (kTargetWorkgroups + items - 1) / items;                 // splits wanted
+        long want = (target + items - 1) / items;                            // splits wanted
         want = std::max(1L, std::min<long>(want, max_pages / 16 > 0 ? max_pages / 16 : 1));
         pps = (int)((max_pages + want - 1) / want);
         pps = (pps + 3) / 4 * 4;
@@ -436,6 +446,7 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(d, B, s));
     a.pages_per_split = s.pages_per_split;
     a.n_splits = s.n_splits;
+    a.wide_cols = s.wide_cols;
     if (int e = kvs::launch_attention(a, stream)) return fail(KVS_ERR_HIP, "attention launch: %s", kvs::hip_error_string(e));
     return KVS_OK;
 }

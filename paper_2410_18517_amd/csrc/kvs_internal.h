@@ -27,6 +27,7 @@ struct AttnArgs {
     float* partials;        // device fp32 [B][T_new][Hq][n_splits][D + 2]
     int32_t* counters;      // device [B][Hkv][n_col_groups], zero between calls
     int32_t pages_per_split, n_splits;
+    int32_t wide_cols;      // prefill: 0 = the page-splitting kernel, else columns per workgroup of the shared-page kernel (64, 128, 256)
 };
 
 struct CopyArgs {

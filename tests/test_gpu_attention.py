@@ -192,10 +192,10 @@ def test_causal_prefill(kb, dtype, Hq, Hkv, d, T_new):
 
 
 # Shapes that reach each instantiation of the shared-page prefill kernel (a workgroup's wavefronts
-# take separate columns and read every page pair from LDS): it is used when one (sequence, kv
-# head) has more than 128 query columns (rows x group size) and there are at least 256 workgroups
-# of 256 columns, or more than 64 columns and 512 workgroups of 128, or at least 64 columns and
-# 512 workgroups of 64 (test_prefill_kernel_boundaries walks the limits).  Ragged column counts, a group size of two,
+# take separate columns and read every page pair from LDS): 256 columns per workgroup when one
+# (sequence, kv head) has more than 128 query columns (rows x group size), 128 for 65 to 128, 64
+# for exactly 64 (test_prefill_kernel_boundaries walks the limits); with few sequences x heads the
+# context is split over workgroups as well (test_causal_prefill's small batches).  Ragged column counts, a group size of two,
 # different start positions per sequence, a permuted page table, a recipient layer.
 @pytest.mark.parametrize("d,Hq,Hkv,B,T_new", [(128, 16, 8, 16, 150),     # 300 columns -> 2 x 256-column workgroups, 8 wavefronts
                                               (128, 16, 8, 16, 100),     # 200 columns -> 4 x 64-column workgroups, 4 wavefronts
@@ -223,8 +223,8 @@ def test_shared_page_prefill_kernels(kb, d, Hq, Hkv, B, T_new):
 
 
 # Column counts on either side of the limits at which the prefill kernels change hands (64, 128 and
-# 256 columns per (sequence, kv head)), with enough workgroups for the shared-page kernels to be chosen:
-# a last column block of a single column leaves wavefronts without any column.
+# 256 columns per (sequence, kv head)): a last column block of a single column leaves wavefronts
+# without any column.
 @pytest.mark.parametrize("Hq,Hkv,B,T_new", [(8, 8, 64, 63), (8, 8, 64, 64), (8, 8, 64, 65), (8, 8, 64, 128), (8, 8, 64, 129),
                                             (16, 8, 32, 127), (16, 8, 32, 128), (16, 8, 32, 129)])
 def test_prefill_kernel_boundaries(kb, Hq, Hkv, B, T_new):
