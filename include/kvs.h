@@ -127,12 +127,12 @@ typedef struct kvs_store {
 } kvs_store;
 
 /* Bytes of the pool; 0 (with kvs_last_error set) if the descriptor is invalid/unsupported.
- * Supported: KVS_BF16 with head_dim 128 or 64 and Hq/Hkv <= 16; KVS_F32 with head_dim a
- * multiple of 64 up to 256. */
+ * Supported: KVS_BF16 and KVS_FP8 with head_dim 128 or 64 and Hq/Hkv <= 16; KVS_F32 with
+ * head_dim a multiple of 64 up to 256. */
 size_t kvs_store_bytes(const kvs_desc* desc);
 
-/* Bytes of scratch the attention calls need for B sequences of up to max_q_rows query rows
- * each (1 for decode).  The scratch holds split-context partial results and per-(sequence,
+/* Bytes of scratch the attention calls need for B sequences of 1 to max_q_rows query rows
+ * each (1 for decode): enough for every row count in that range.  The scratch holds split-context partial results and per-(sequence,
  * kv head) arrival counters; the caller zero-fills it once after allocating it, and every
  * call leaves the counters zero again.  Calls sharing one workspace must not overlap. */
 size_t kvs_workspace_bytes(const kvs_desc* desc, int B, int max_q_rows);

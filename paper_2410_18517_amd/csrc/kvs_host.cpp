@@ -267,11 +267,22 @@ size_t kvs_workspace_bytes(const kvs_desc* d, int B, int max_q_rows)
 {
     if (check_desc(d) != KVS_OK) return 0;
     if (B <= 0 || max_q_rows <= 0) { fail(KVS_ERR_INVALID_ARG, "B and max_q_rows must be positive"); return 0; }
-    size_t need = 0;
-    const int rows[2] = {1, max_q_rows};
-    for (int r : rows) {
+    // The largest need over every row count a call may bring: fewer rows can mean more context
+    // splits, so the need does not grow monotonically with the rows.  Once the rows alone give
+    // enough workgroups nothing is split any more (and a forced split is the same for all row
+    // counts), and the need only grows with the rows from there on: the walk stops there.
+    const long capacity = (long)d->max_blocks_per_seq * KVS_BLOCK_TOKENS;
+    const int last = (int)std::min<long>(max_q_rows, capacity);
+    const int group = d->Hq / d->Hkv;
+    auto need_for = [&](int r) {
         const Split s = choose_split(d, B, r);
-        need = std::max(need, counter_bytes(d, B, s) + partial_floats(d, B, r, s) * sizeof(float));
+        return counter_bytes(d, B, s) + partial_floats(d, B, r, s) * sizeof(float);
+    };
+    size_t need = need_for(last);
+    if (g_split_tokens.load() > 0 || d->dtype == KVS_F32) return std::max(need, need_for(1));
+    for (int r = 1; r < last; ++r) {
+        need = std::max(need, need_for(r));
+        if ((long)r * group > 128 && choose_split(d, B, r).n_splits == 1) break;
     }
     return need;
 }

@@ -3,6 +3,8 @@
 Tolerance (both stores): every output vector within 5e-3 relative L2 of the oracle; fp32 stores
 are held to 1e-5.  Edge cases: empty, one-token, page-boundary and ragged lengths, one and many
 context splits, recipients (incl. the last layer), donors with several recipients."""
+import ctypes as C
+
 import numpy as np
 import pytest
 import torch
@@ -198,7 +200,7 @@ def test_causal_prefill(kb, dtype, Hq, Hkv, d, T_new):
 # context is split over workgroups as well (test_causal_prefill's small batches).  Ragged column counts, a group size of two,
 # different start positions per sequence, a permuted page table, a recipient layer.
 @pytest.mark.parametrize("d,Hq,Hkv,B,T_new", [(128, 16, 8, 16, 150),     # 300 columns -> 2 x 256-column workgroups, 8 wavefronts
-                                              (128, 16, 8, 16, 100),     # 200 columns -> 4 x 64-column workgroups, 4 wavefronts
+                                              (128, 16, 8, 16, 100),     # 200 columns -> one 256-column workgroup, a quarter of it idle
                                               (64, 8, 8, 16, 300),       # head size 64, one query head per kv head
                                               (64, 16, 8, 16, 100)])
 def test_shared_page_prefill_kernels(kb, d, Hq, Hkv, B, T_new):
@@ -220,6 +222,54 @@ def test_shared_page_prefill_kernels(kb, d, Hq, Hkv, B, T_new):
     tail = 8
     short = kb.kvs_prefill_attention(case.store, 1, q[:, -tail:].contiguous().cuda(), start + (T_new - tail)).cpu().numpy()
     assert rel_l2_rows(short, got[:, -tail:].astype(np.float64)).max() <= REL_L2_ATTENTION
+
+
+# Few (sequence, kv head) pairs: the shared-page kernels split the context over workgroups too, and
+# the last workgroup of a column block to arrive merges the states.  By the host's own choice at a
+# long context, and with a forced split of 4 or 8 pages at a short one; start positions that leave
+# the later splits of a sequence without any visible key, or cut a split in the middle.
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("Hq,Hkv,B,T_new,cap,split_tokens", [(8, 2, 3, 16, 2048, 0),      # 64 columns, 8 splits
+                                                             (8, 2, 3, 30, 2048, 0),      # 120 columns -> the 128-column shape
+                                                             (16, 2, 3, 40, 2048, 0),     # 320 columns -> 2 blocks of 256
+                                                             (8, 2, 3, 16, 416, 64),      # 7 splits of 2 page pairs
+                                                             (8, 1, 2, 31, 416, 128),     # 248 columns, 4 splits of 4 pairs
+                                                             (4, 4, 3, 97, 416, 64)])     # one head per group, 128-column shape
+def test_shared_page_prefill_with_context_splits(kb, dtype, Hq, Hkv, B, T_new, cap, split_tokens):
+    d = 128
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, 2, Hq, Hkv, d, B, dtype, cap, share, paged=True, seed=67)
+    start = np.array([0, cap // 3 + 5, cap - T_new][:B], np.int32)
+    start[-1] = cap - T_new
+    q = case.q(1, rows=T_new)
+    assert kb.lib().kvs_set_split_tokens(split_tokens) == kb.KVS_OK
+    try:
+        for _ in range(2):                                         # twice: the counters must be left at zero
+            got = kb.kvs_prefill_attention(case.store, 1, q.cuda(), start).cpu().numpy()
+            want = orc.shared_attention(1, share, [case.K[0], None], [case.V[0], None], inputs.to_oracle_array(q), start)
+            assert np.isfinite(got).all()
+            assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
+    finally:
+        assert kb.lib().kvs_set_split_tokens(0) == kb.KVS_OK
+
+
+# A workspace sized for up to 33 rows must serve a call of 32: with 64 (sequence, kv head) pairs, 33
+# rows x 4 heads take the 256-column shape with 4 context splits, 32 rows the 128-column shape with
+# 8, which needs more partial states than either end of the range.
+def test_workspace_for_a_row_range_serves_every_row_count(kb):
+    Hq, Hkv, B, cap, d = 32, 8, 8, 2048, 128
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, 2, Hq, Hkv, d, B, "bf16", cap, share, paged=True, seed=71)
+    need = kb.lib().kvs_workspace_bytes(C.byref(case.store.desc), B, 33)
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    start = np.full(B, cap - 64, np.int32)
+    for T_new in (33, 32, 16, 1):
+        q = case.q(1, rows=T_new)
+        got = kb.kvs_prefill_attention(case.store, 1, q.cuda(), start, workspace=ws).cpu().numpy()
+        for b in (0, B - 1):
+            want = orc.shared_attention(1, share, [case.K[0][b:b + 1], None], [case.V[0][b:b + 1], None],
+                                        inputs.to_oracle_array(q[b:b + 1]), start[b:b + 1])
+            assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, (T_new, b)
 
 
 # Column counts on either side of the limits at which the prefill kernels change hands (64, 128 and

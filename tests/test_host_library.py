@@ -120,6 +120,24 @@ def test_store_and_workspace_sizes():
     assert lib.kvs_project_workspace_bytes(C.byref(_desc(dtype=kb.KVS_F32)), 4096, 4, 1) == 0
 
 
+def test_workspace_covers_every_row_count_up_to_the_maximum():
+    """Fewer rows can mean more context splits and so more partial states: the size for a range of
+    row counts must not shrink when the range grows (33 rows against 32 at 64 (sequence, kv head)
+    pairs is such a place: the kernel shape changes there and the splits halve)."""
+    lib = kb.lib()
+    for kw, B in ((dict(Hq=32, Hkv=8, max_blocks_per_seq=128, num_blocks=1024), 8),
+                  (dict(Hq=32, Hkv=8, max_blocks_per_seq=2048, num_blocks=8192), 4),
+                  (dict(Hq=40, Hkv=40, max_blocks_per_seq=128, num_blocks=2048), 16),
+                  (dict(Hq=8, Hkv=1, max_blocks_per_seq=4096, num_blocks=4096), 1)):
+        d = _desc(**kw)
+        sizes = [lib.kvs_workspace_bytes(C.byref(d), B, r) for r in range(1, 300)]
+        assert all(s > 0 for s in sizes)
+        assert all(a <= b for a, b in zip(sizes, sizes[1:])), kw
+    d = _desc(Hq=32, Hkv=8, max_blocks_per_seq=128, num_blocks=1024)
+    assert lib.kvs_workspace_bytes(C.byref(d), 8, 33) == lib.kvs_workspace_bytes(C.byref(d), 8, 32)
+    assert lib.kvs_workspace_bytes(C.byref(d), 8, 1 << 30) > 0          # beyond the capacity: as at the capacity
+
+
 def _fake_store(share=(0, 1, 2, 1), slots=(0, 1, 2, 1), **kw):
     """A store whose device pointers are junk: valid only for calls that fail before any launch."""
     hs, hl = np.asarray(share, np.int32), np.asarray(slots, np.int32)
