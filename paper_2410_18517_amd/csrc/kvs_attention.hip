@@ -16,6 +16,7 @@ namespace {
 
 constexpr int kWaves = 4;              // wavefronts per workgroup of the bf16 kernel
 constexpr int kThreads = kWaves * 64;
+constexpr int kMinAdaptivePages = 16;  // a split sized on the device never gets fewer pages than this
 constexpr float kRefSlack = 8.f;       // log2 units a score may exceed the softmax reference by
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -108,7 +109,10 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a)
 // kPrefetch pages in flight, and keeps a private online-softmax state.  The states merge
 // through LDS at the end; with more than one split the merged, unnormalised state goes to
 // the partials buffer, and the last workgroup to finish a (sequence, kv head, column group)
-// folds its splits into the output.
+// folds its splits into the output.  The host fixes the number of split indices from the
+// store's capacity (it never sees the lengths); a decode launch then sizes the page range of a
+// split by the lengths it finds on the device, so that a batch far below the capacity still
+// spreads over as many workgroups as a full one.
 //
 // MFMA roles.  Scores: S[token][column] = K_page(16 x D) . Q^T(D x 16) with
 // v_mfma_f32_16x16x32_bf16; lane l holds the scores of column l%16 for tokens 4*(l/16)..+3 of
@@ -469,19 +473,20 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     const int group = st.Hq / st.Hkv;
     const int ncols = a.T_new * group;
     const int cap = st.max_blocks_per_seq * kPageTokens;
-    const int page_lo = split * a.pages_per_split;
-    const int my_first = page_lo + wave;
+    const int guessed_first = split * a.pages_per_split + wave;
 
     // Start-up look-ups in one round trip: a single vector load in which lane 0 fetches the
     // sequence length, lane 1 the layer's donor, lanes 2..7 the page-table entries of the first
     // pages (index clamped into the table, so they can be fetched before the length says how
     // many are used) and lanes 8..63 the slots of layers 0..55; the values are then read out of
-    // the lanes.  Only a donor beyond layer 55 costs a second, dependent look-up.
+    // the lanes.  Only a donor beyond layer 55 costs a second, dependent look-up.  The first
+    // pages are those of the split the host would give full sequences; see below.
     static_assert(kPrefetch <= 6, "lanes 2..7 carry the first page-table entries");
+    static_assert(NT > 1 || kPrefetch * kWaves <= kMinAdaptivePages, "a split sized on the device holds the first pages of every wavefront");
     int first_page[kPrefetch];
 #pragma unroll
     for (int j = 0; j < kPrefetch; ++j) {
-        const int pg = my_first + j * kWaves;
+        const int pg = guessed_first + j * kWaves;
         first_page[j] = pg < st.max_blocks_per_seq ? pg : st.max_blocks_per_seq - 1;
     }
     const int32_t* look = nullptr;
@@ -494,6 +499,22 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
         if (st.block_table && lane - 2 < kPrefetch) look = st.block_table + (size_t)b * st.max_blocks_per_seq + pg;
     } else if (lane - 8 < st.L) look = st.slot_of_layer + (lane - 8);
     const int looked = look ? *look : 0;
+    // A decode launch sizes its splits by the lengths it finds (a.adaptive): every workgroup reads
+    // all of them, in the same round trip as the look-ups above, and derives the same pages per
+    // split further down.
+    const bool carries_new = NT == 1 && !kFp8 && a.k_new != nullptr;
+    const bool adaptive = NT == 1 && a.adaptive;
+    const int n_len = a.lens_per_head ? a.B * st.Hkv : a.B;
+    int len_sum = 0, len_longest = 0;             // in pages, this lane's share of the lengths
+    if (adaptive) {
+        for (int i = lane; i < n_len; i += 64) {
+            int n = a.lens[i] + a.lens_bias - (carries_new ? 1 : 0);
+            n = n < 0 ? 0 : (n > cap ? cap : n);
+            const int pg = (n + kPageTokens - 1) / kPageTokens;
+            len_sum += pg;
+            len_longest = pg > len_longest ? pg : len_longest;
+        }
+    }
     const int len_raw = __builtin_amdgcn_readlane(looked, 0);
     const int donor_raw = __builtin_amdgcn_readlane(looked, 1);
     int first_blk[kPrefetch];
@@ -534,7 +555,6 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     // A decode step that carries its own new token (k_new, v_new): the pages hold the tokens before
     // it, the token itself joins the softmax in the merge below (split 0) and is written to its
     // place in the store on the side -- no separate append launch, and nothing here waits for the write.
-    const bool carries_new = NT == 1 && !kFp8 && a.k_new != nullptr;
     const int new_pos = len_raw - 1;
     const bool has_new = carries_new && new_pos >= 0 && new_pos < cap;
 
@@ -552,20 +572,74 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     const int n_min = n0 + c_lo / group;          // fewest keys any of its rows sees
     const int n_max = n0 + c_hi / group;          // most keys, = tokens certainly stored
     const int pages_total = (n_max + kPageTokens - 1) / kPageTokens;
-    int page_hi = page_lo + a.pages_per_split;
+
+    // Where the launch does not size its splits itself, or this sequence fills its table (then the
+    // sizing below most likely ends at the host's figure), the first pages go out at once, for the
+    // split the host would give full sequences (what the look-up above fetched the page-table
+    // entries for) ...
+    const void* pool = st.pool;
+    using Raw = std::conditional_t<kFp8, PageRegs8<D>, PageRegs<D>>;    // a page as it sits in the store
+    Raw buf[kPrefetch];
+    const bool guess_early = !adaptive || pages_total + 4 * a.want_splits > st.max_blocks_per_seq;
+    if (guess_early) {
+        int hi = guessed_first - wave + a.pages_per_split;
+        if (hi > pages_total) hi = pages_total;
+        const int guessed_pages = guessed_first < hi ? (hi - guessed_first + kWaves - 1) / kWaves : 0;
+#pragma unroll
+        for (int j = 0; j < kPrefetch; ++j)
+            if (j < guessed_pages) load_page(buf[j], pool, page_offset(st, slot, first_blk[j], g), lane);
+    }
+    // ... and while they travel the launch's pages per split are worked out from all its lengths:
+    // the mean length shared out as the host shares out a full sequence, so that about as many
+    // workgroups carry keys whatever the lengths are, but never so few pages that the longest
+    // sequence would need more splits than the grid has.  Every workgroup derives the same number.
+    int pps = a.pages_per_split;
+    if (adaptive) {
+        int sum = len_sum, longest = len_longest;
+        if (n_len <= 16) {                       // one length per lane: read the lanes out, add on the scalar side
+            sum = 0;
+            longest = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int pg = __builtin_amdgcn_readlane(len_sum, i);
+                sum += pg;
+                longest = pg > longest ? pg : longest;
+            }
+        } else {                                 // lanes from n_len on hold zero: lane 0 ends with all of it
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                if (off >= n_len) continue;
+                sum += __shfl_xor(sum, off);
+                const int other = __shfl_xor(longest, off);
+                longest = other > longest ? other : longest;
+            }
+            sum = __builtin_amdgcn_readfirstlane(sum);
+            longest = __builtin_amdgcn_readfirstlane(longest);
+        }
+        const int sharers = n_len * a.want_splits;
+        const int share = ((sum + sharers - 1) / sharers + 3) & ~3;
+        const int fit = ((longest + a.n_splits - 1) / a.n_splits + 3) & ~3;
+        pps = share > fit ? share : fit;
+        pps = pps > kMinAdaptivePages ? pps : kMinAdaptivePages;
+    }
+    const int page_lo = split * pps;
+    const int my_first = page_lo + wave;
+    int page_hi = page_lo + pps;
     if (page_hi > pages_total) page_hi = pages_total;
     const int my_pages = my_first < page_hi ? (page_hi - my_first + kWaves - 1) / kWaves : 0;
     // Splits that hold keys for this (sequence, column group).  Workgroups past them leave at
     // once; if there is at most one, split 0 writes the output itself and no state is published.
-    const int live_splits = (pages_total + a.pages_per_split - 1) / a.pages_per_split;
+    const int live_splits = (pages_total + pps - 1) / pps;
     if (split > 0 && split >= live_splits) return;
-
-    const void* pool = st.pool;
-    using Raw = std::conditional_t<kFp8, PageRegs8<D>, PageRegs<D>>;    // a page as it sits in the store
-    Raw buf[kPrefetch];
+    // Where nothing was guessed, or the lengths moved this split, its own first pages are loaded (a split
+    // that starts where it was guessed to has the same first pages: neither size is below
+    // kPrefetch pages per wavefront, so only the sequence's end can cut them short).
+    if (!guess_early || my_first != guessed_first) {
 #pragma unroll
-    for (int j = 0; j < kPrefetch; ++j)
-        if (j < my_pages) load_page(buf[j], pool, page_offset(st, slot, first_blk[j], g), lane);
+        for (int j = 0; j < kPrefetch; ++j)
+            if (j < my_pages)
+                load_page(buf[j], pool, page_offset(st, slot, safe_block_of(st, b, my_first + j * kWaves), g), lane);
+    }
 
     const float scale_log2 = 1.44269504088896340736f * (D == 128 ? 0.08838834764831845f : 0.125f);
     float m[NT], l[NT];

@@ -128,13 +128,20 @@ kvs::StoreView view_of(const kvs_store* s, int layer)
 // Query columns (row, head-in-group pairs) one workgroup of the bf16 kernel covers.
 int columns_per_workgroup(int T_new) { return T_new > 1 ? 64 : 16; }
 
-struct Split { int pages_per_split, n_splits, n_col_groups, wide_cols; };
+struct Split { int pages_per_split, n_splits, n_col_groups, wide_cols, adaptive, want_splits; };
+
+// A decode launch sizes its splits on the device, by the lengths it finds there (the host never
+// sees them): the grid carries this many times the split indices a batch of full sequences needs,
+// so that a sequence longer than the batch's mean can take more workgroups than a shorter one.
+constexpr int kSplitHeadroom = 1;
 
 Split choose_split(const kvs_desc* d, int B, int T_new)
 {
     Split s;
     const int max_pages = d->max_blocks_per_seq;
     s.wide_cols = 0;
+    s.adaptive = 0;
+    s.want_splits = 1;
     if (d->dtype == KVS_F32) {           // the fp32 kernel walks the whole context in one wave
         s.pages_per_split = max_pages;
         s.n_splits = 1;
@@ -155,17 +162,29 @@ Split choose_split(const kvs_desc* d, int B, int T_new)
     }
     int pps;
     const int forced = g_split_tokens.load();
+    const long most = max_pages / 16 > 0 ? max_pages / 16 : 1;               // no split below 16 pages
+    long want = 1;
     if (forced > 0) {
         pps = forced / KVS_BLOCK_TOKENS;
     } else {
-        long want = (target + items - 1) / items;                            // splits wanted
-        want = std::max(1L, std::min<long>(want, max_pages / 16 > 0 ? max_pages / 16 : 1));
+        want = (target + items - 1) / items;                                 // splits wanted
+        want = std::max(1L, std::min(want, most));
         pps = (int)((max_pages + want - 1) / want);
         pps = (pps + 3) / 4 * 4;
     }
     pps = std::max(kMinPagesPerSplit, std::min(pps, (max_pages + 3) / 4 * 4));
     s.pages_per_split = pps;
     s.n_splits = (max_pages + pps - 1) / pps;
+    // (with more than two workgroups per compute unit the order in which they are handed out evens
+    // out unequal lengths by itself, and every workgroup would scan that many more lengths)
+    if (T_new == 1 && forced == 0 && items <= 2 * kTargetWorkgroups) {
+        const int spare = (int)std::min(most, kSplitHeadroom * want);
+        if (spare > 1) {
+            s.adaptive = 1;
+            s.want_splits = (int)want;
+            s.n_splits = std::max(s.n_splits, spare);
+        }
+    }
     return s;
 }
 
@@ -458,6 +477,8 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     a.pages_per_split = s.pages_per_split;
     a.n_splits = s.n_splits;
     a.wide_cols = s.wide_cols;
+    a.adaptive = s.adaptive;
+    a.want_splits = s.want_splits;
     if (int e = kvs::launch_attention(a, stream)) return fail(KVS_ERR_HIP, "attention launch: %s", kvs::hip_error_string(e));
     return KVS_OK;
 }

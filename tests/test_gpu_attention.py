@@ -109,6 +109,54 @@ def test_many_splits_merge_is_exact_and_repeatable(kb):
         kb.kvs_set_split_tokens(0)
 
 
+# A decode launch sizes its context splits by the lengths it finds on the device: a batch far below
+# the store's capacity, one long sequence among short ones, and a wide spread (with an empty
+# sequence, a one-token one and a full one) each move the splits away from where the host's choice
+# for full sequences would put them.  The plain call, the per-head lengths of a sparsified slot
+# (each head of a sequence its own length) and the one-launch decode step all take that path.
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("kind", ["spread", "short", "one_long"])
+def test_decode_splits_follow_the_lengths(kb, dtype, kind):
+    L, Hq, Hkv, d, B, cap = 2, 16, 8, 128, 16, 2048
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, dtype, cap, share, paged=True, seed=97)
+    rng = np.random.default_rng(97)
+    if kind == "spread":
+        lens = rng.integers(0, cap + 1, size=B).astype(np.int32)
+        lens[:4] = [cap, 0, 1, 16]
+    elif kind == "short":
+        lens = rng.integers(480, 520, size=B).astype(np.int32)
+    else:
+        lens = np.full(B, 40, np.int32)
+        lens[5] = cap
+    q = case.q(1)
+    qo = inputs.to_oracle_array(q)
+    for _ in range(2):                                             # twice: counters are left at zero
+        got = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens).cpu().numpy()
+        want = orc.decode_attention(1, share, case.K, case.V, qo, lens)
+        assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
+    # per-head lengths: head g of sequence b keeps the first head_lens[b, g] tokens
+    head_lens = np.stack([np.roll(lens, g) for g in range(Hkv)], axis=1).astype(np.int32)      # [B, Hkv]
+    got = kb.kvs_decode_attention_per_head(case.store, 1, q.cuda(), head_lens[None]).cpu().numpy()
+    group = Hq // Hkv
+    for g in range(Hkv):
+        want = orc.decode_attention(1, share, case.K, case.V, qo, head_lens[:, g])
+        assert rel_l2_rows(got[:, g * group:(g + 1) * group], want[:, g * group:(g + 1) * group]).max() <= REL_L2_ATTENTION, g
+    # the decode step that stores its own token (lengths count it, so at least one)
+    step_lens = np.maximum(lens, 1)
+    row_dt = case.row_dtype
+    k_new = inputs.normal((B, 1, Hkv, d), 97, 700, dtype=row_dt)
+    v_new = inputs.normal((B, 1, Hkv, d), 97, 701, dtype=row_dt)
+    got = kb.kvs_decode_step(case.store, 0, q.cuda(), k_new.cuda(), v_new.cuda(), step_lens).cpu().numpy()
+    ko, vo = inputs.to_oracle_array(k_new), inputs.to_oracle_array(v_new)
+    if dtype == "fp8":
+        from helpers import stored_fp8
+        ko, vo = stored_fp8(ko), stored_fp8(vo)
+    assert orc.append_kv(0, share, case.K, case.V, ko, vo, step_lens - 1)
+    want = orc.decode_attention(0, share, case.K, case.V, qo, step_lens)
+    assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
+
+
 @pytest.mark.parametrize("gain", [0.05, 4.0, 24.0])
 def test_bf16_flat_and_peaked_softmax(kb, gain):
     """Scores from nearly constant to widely spread (the running reference of the exponentials has
