@@ -130,9 +130,11 @@ int columns_per_workgroup(int T_new) { return T_new > 1 ? 64 : 16; }
 
 struct Split { int pages_per_split, n_splits, n_col_groups, wide_cols, adaptive, want_splits; };
 
-// A decode launch sizes its splits on the device, by the lengths it finds there (the host never
-// sees them): the grid carries this many times the split indices a batch of full sequences needs,
-// so that a sequence longer than the batch's mean can take more workgroups than a shorter one.
+// A decode launch sizes the page range of a split on the device, by the lengths it finds there
+// (the host never sees them); the host only fixes how many split indices the grid carries: this
+// many times what a batch of full sequences needs.  More than 1 would let a sequence longer than
+// the batch's mean take more workgroups than a shorter one; measured, that gains nothing on mixed
+// lengths and costs the full store the start-up of the workgroups that only leave.
 constexpr int kSplitHeadroom = 1;
 
 Split choose_split(const kvs_desc* d, int B, int T_new)
