@@ -109,10 +109,11 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a)
 // kPrefetch pages in flight, and keeps a private online-softmax state.  The states merge
 // through LDS at the end; with more than one split the merged, unnormalised state goes to
 // the partials buffer, and the last workgroup to finish a (sequence, kv head, column group)
-// folds its splits into the output.  The host fixes the number of split indices from the
-// store's capacity (it never sees the lengths); a decode launch then sizes the page range of a
-// split by the lengths it finds on the device, so that a batch far below the capacity still
-// spreads over as many workgroups as a full one.
+// folds its splits into the output.  The host sizes the grid from the store's capacity (it
+// never sees the lengths); a decode launch then sizes the page range of a split by the lengths
+// it finds on the device, so that a batch far below the capacity still spreads over as many
+// workgroups as a full one, and, with one length per sequence, also decides there which
+// (sequence, split) each workgroup takes (grid = (Hkv, items); see the kernel).
 //
 // MFMA roles.  Scores: S[token][column] = K_page(16 x D) . Q^T(D x 16) with
 // v_mfma_f32_16x16x32_bf16; lane l holds the scores of column l%16 for tokens 4*(l/16)..+3 of
@@ -254,10 +255,12 @@ __device__ __forceinline__ bool arrived_last(int* counter, int live_splits)
 }
 
 // Merge of the published states of `live_splits` splits for the columns [first_col, first_col +
-// n_cols) of (sequence b, kv head g): the normalised output rows.
+// n_cols) of (sequence b, kv head g): the normalised output rows.  The record of (output row,
+// split s) is number row * rec_per_row + s * rec_per_split + rec_first.
 template <int D>
 __device__ __forceinline__ void merge_splits(const AttnArgs& a, int b, int g, int first_col, int n_cols, int ncols,
-                                             int group, int live_splits, int n_threads)
+                                             int group, int live_splits, int n_threads,
+                                             int rec_per_row, int rec_per_split, size_t rec_first)
 {
     const StoreView& st = a.st;
     for (int idx = threadIdx.x; idx < n_cols * (D / 4); idx += n_threads) {
@@ -266,16 +269,17 @@ __device__ __forceinline__ void merge_splits(const AttnArgs& a, int b, int g, in
         if (cidx >= ncols) break;
         const int r = cidx / group, hc = cidx % group;
         const size_t row = ((size_t)b * a.T_new + r) * st.Hq + g * group + hc;
-        const float* part = a.partials + row * a.n_splits * (size_t)(D + 2);
+        const float* part = a.partials + (row * rec_per_row + rec_first) * (size_t)(D + 2);
+        const size_t step = (size_t)rec_per_split * (D + 2);
         float M = -INFINITY;
 #pragma unroll 8
-        for (int s = 0; s < live_splits; ++s) M = fmaxf(M, fetch_pair(part + s * (D + 2) + D)[0]);
+        for (int s = 0; s < live_splits; ++s) M = fmaxf(M, fetch_pair(part + s * step + D)[0]);
         const float M_use = M == -INFINITY ? 0.f : M;
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
         float lt = 0.f;
 #pragma unroll 4
         for (int s = 0; s < live_splits; ++s) {
-            const float* ps = part + s * (D + 2);
+            const float* ps = part + s * step;
             const floatx2 ml = fetch_pair(ps + D);
             const floatx2 lo = fetch_pair(ps + d4);
             const floatx2 hi = fetch_pair(ps + d4 + 2);
@@ -467,12 +471,34 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     // Workgroup ids go round-robin over the chip's eight XCDs, so the fastest-varying index
     // must be one whose every value carries work: the kv head.  A split index there would
     // park whole XCDs on the empty splits of short sequences.
-    const int g = blockIdx.x, b = blockIdx.y;
-    const int split = NT == 1 ? (int)blockIdx.z : (int)blockIdx.z % a.n_splits;   // one decode row: one column group
+    //
+    // Which (sequence, split) a workgroup takes.  Prefill, per-head lengths and a forced split:
+    // the grid says it (blockIdx.y = sequence, blockIdx.z = split, and column group), with a fixed
+    // (or, a.adaptive == 1, device-sized) page range per split; workgroups past a sequence's last
+    // split leave at once.  A decode launch with one length per sequence (a.adaptive == 2) instead
+    // numbers its work items itself, from the lengths it finds: blockIdx.y is an item, the items
+    // of sequence 0 come first, then those of sequence 1 and so on, each sequence as many as its
+    // length asks for.  The workgroups that carry keys are then the first ones of the grid
+    // whatever the lengths are.  That matters because workgroups are placed on the compute units
+    // in turn whether they stay or leave at once: with the ones that leave scattered among the
+    // others, the later splits of one long sequence among short ones doubled up on a quarter of
+    // the units (measured: 52 us where 30 us were due).  Until the lengths are there the item is
+    // taken for what it would be if every sequence were full, and everything that can be fetched
+    // on that guess is fetched in the same round trip as the lengths.
+    const int g = blockIdx.x;
+    const bool compact = NT == 1 && a.adaptive == 2;
+    const int item = blockIdx.y;
+    int b = blockIdx.y, split = NT == 1 ? (int)blockIdx.z : (int)blockIdx.z % a.n_splits;
+    if (compact) {                                     // a.n_splits: the splits of a full sequence
+        b = item / a.n_splits;
+        split = item - b * a.n_splits;
+        if (b >= a.B) { b = a.B - 1; split = a.n_splits; }   // beyond a batch of full sequences: nothing to fetch early
+    }
     const int cgrp = NT == 1 ? 0 : (int)blockIdx.z / a.n_splits;
     const int group = st.Hq / st.Hkv;
     const int ncols = a.T_new * group;
     const int cap = st.max_blocks_per_seq * kPageTokens;
+    const int guessed_b = b;
     const int guessed_first = split * a.pages_per_split + wave;
 
     // Start-up look-ups in one round trip: a single vector load in which lane 0 fetches the
@@ -480,7 +506,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     // pages (index clamped into the table, so they can be fetched before the length says how
     // many are used) and lanes 8..63 the slots of layers 0..55; the values are then read out of
     // the lanes.  Only a donor beyond layer 55 costs a second, dependent look-up.  The first
-    // pages are those of the split the host would give full sequences; see below.
+    // pages are those of the split the host would give full sequences.
     static_assert(kPrefetch <= 6, "lanes 2..7 carry the first page-table entries");
     static_assert(NT > 1 || kPrefetch * kWaves <= kMinAdaptivePages, "a split sized on the device holds the first pages of every wavefront");
     int first_page[kPrefetch];
@@ -501,21 +527,25 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     const int looked = look ? *look : 0;
     // A decode launch sizes its splits by the lengths it finds (a.adaptive): every workgroup reads
     // all of them, in the same round trip as the look-ups above, and derives the same pages per
-    // split further down.
+    // split further down.  lens_lane: what the length array holds for sequence `lane` (compact
+    // launches have at most 64 sequences).
     const bool carries_new = NT == 1 && !kFp8 && a.k_new != nullptr;
     const bool adaptive = NT == 1 && a.adaptive;
     const int n_len = a.lens_per_head ? a.B * st.Hkv : a.B;
     int len_sum = 0, len_longest = 0;             // in pages, this lane's share of the lengths
+    int lens_lane = 0;
     if (adaptive) {
         for (int i = lane; i < n_len; i += 64) {
-            int n = a.lens[i] + a.lens_bias - (carries_new ? 1 : 0);
+            const int raw = a.lens[i];
+            if (i == lane) lens_lane = raw;
+            int n = raw + a.lens_bias - (carries_new ? 1 : 0);
             n = n < 0 ? 0 : (n > cap ? cap : n);
             const int pg = (n + kPageTokens - 1) / kPageTokens;
             len_sum += pg;
             len_longest = pg > len_longest ? pg : len_longest;
         }
     }
-    const int len_raw = __builtin_amdgcn_readlane(looked, 0);
+    int len_raw = __builtin_amdgcn_readlane(looked, 0);
     const int donor_raw = __builtin_amdgcn_readlane(looked, 1);
     int first_blk[kPrefetch];
 #pragma unroll
@@ -524,54 +554,55 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
         first_blk[j] = blk < 0 ? 0 : (blk >= st.num_blocks ? st.num_blocks - 1 : blk);
     }
 
-    // columns of this lane, one per tile, and their query fragments (B operand of the score MFMA)
-    size_t q_off[NT];
-    bool col_ok[NT];
-    int col_row[NT];
-#pragma unroll
-    for (int ct = 0; ct < NT; ++ct) {
-        const int cidx = (cgrp * NT + ct) * 16 + col;
-        col_ok[ct] = cidx < ncols;
-        col_row[ct] = col_ok[ct] ? cidx / group : 0;
-        const int hc = col_ok[ct] ? cidx % group : 0;
-        q_off[ct] = (((size_t)b * a.T_new + col_row[ct]) * st.Hq + g * group + hc) * D;
-    }
-    bf16x8 qf[NT][KS];
-    const unsigned short* qbase = static_cast<const unsigned short*>(a.q);
-#pragma unroll
-    for (int ct = 0; ct < NT; ++ct)
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            uint4 w = make_uint4(0, 0, 0, 0);
-            if (col_ok[ct]) w = *reinterpret_cast<const uint4*>(qbase + q_off[ct] + s * 32 + quad * 8);
-            qf[ct][s] = __builtin_bit_cast(bf16x8, w);
-        }
-
     // the strategy's substitution: this layer reads the slot of its donor (itself if none)
     const int donor = donor_raw < 0 ? 0 : (donor_raw >= st.L ? st.L - 1 : donor_raw);
     const int slot_raw = donor < 56 ? __builtin_amdgcn_readlane(looked, 8 + donor) : st.slot_of_layer[donor];
     const int slot = slot_raw < 0 ? 0 : (slot_raw >= st.n_slots ? st.n_slots - 1 : slot_raw);
 
-    // A decode step that carries its own new token (k_new, v_new): the pages hold the tokens before
-    // it, the token itself joins the softmax in the merge below (split 0) and is written to its
-    // place in the store on the side -- no separate append launch, and nothing here waits for the write.
-    const int new_pos = len_raw - 1;
-    const bool has_new = carries_new && new_pos >= 0 && new_pos < cap;
-
-    // keys visible to query row 0; row r sees n0 + r
-    int n0 = len_raw + a.lens_bias - (carries_new ? 1 : 0);
-    n0 = n0 < 0 ? 0 : n0;
-    if (n0 > cap - (a.T_new - 1)) n0 = cap - (a.T_new - 1);
+    // What depends on the sequence: the columns of this lane, one per tile, with their query
+    // fragments (B operand of the score MFMA), and the keys its rows see.
+    bool col_ok[NT];
+    int col_row[NT];
+    bf16x8 qf[NT][KS];
+    const unsigned short* qbase = static_cast<const unsigned short*>(a.q);
+    int n0, n_min, n_max, pages_total, new_pos;
+    bool has_new;
     int n_col[NT];
+    auto sequence_setup = [&]() {
 #pragma unroll
-    for (int ct = 0; ct < NT; ++ct) n_col[ct] = n0 + col_row[ct];
-    // rows covered by the workgroup bound the pages it needs
-    const int c_lo = cgrp * NT * 16;
-    int c_hi = c_lo + NT * 16 - 1;
-    if (c_hi > ncols - 1) c_hi = ncols - 1;
-    const int n_min = n0 + c_lo / group;          // fewest keys any of its rows sees
-    const int n_max = n0 + c_hi / group;          // most keys, = tokens certainly stored
-    const int pages_total = (n_max + kPageTokens - 1) / kPageTokens;
+        for (int ct = 0; ct < NT; ++ct) {
+            const int cidx = (cgrp * NT + ct) * 16 + col;
+            col_ok[ct] = cidx < ncols;
+            col_row[ct] = col_ok[ct] ? cidx / group : 0;
+            const int hc = col_ok[ct] ? cidx % group : 0;
+            const size_t q_off = (((size_t)b * a.T_new + col_row[ct]) * st.Hq + g * group + hc) * D;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                uint4 w = make_uint4(0, 0, 0, 0);
+                if (col_ok[ct]) w = *reinterpret_cast<const uint4*>(qbase + q_off + s * 32 + quad * 8);
+                qf[ct][s] = __builtin_bit_cast(bf16x8, w);
+            }
+        }
+        // A decode step that carries its own new token (k_new, v_new): the pages hold the tokens before
+        // it, the token itself joins the softmax in the merge below (split 0) and is written to its
+        // place in the store on the side -- no separate append launch, and nothing here waits for the write.
+        new_pos = len_raw - 1;
+        has_new = carries_new && new_pos >= 0 && new_pos < cap;
+        // keys visible to query row 0; row r sees n0 + r
+        n0 = len_raw + a.lens_bias - (carries_new ? 1 : 0);
+        n0 = n0 < 0 ? 0 : n0;
+        if (n0 > cap - (a.T_new - 1)) n0 = cap - (a.T_new - 1);
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) n_col[ct] = n0 + col_row[ct];
+        // rows covered by the workgroup bound the pages it needs
+        const int c_lo = cgrp * NT * 16;
+        int c_hi = c_lo + NT * 16 - 1;
+        if (c_hi > ncols - 1) c_hi = ncols - 1;
+        n_min = n0 + c_lo / group;          // fewest keys any of its rows sees
+        n_max = n0 + c_hi / group;          // most keys, = tokens certainly stored
+        pages_total = (n_max + kPageTokens - 1) / kPageTokens;
+    };
+    sequence_setup();
 
     // Where the launch does not size its splits itself, or this sequence fills its table (then the
     // sizing below most likely ends at the host's figure), the first pages go out at once, for the
@@ -591,9 +622,9 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     }
     // ... and while they travel the launch's pages per split are worked out from all its lengths:
     // the mean length shared out as the host shares out a full sequence, so that about as many
-    // workgroups carry keys whatever the lengths are, but never so few pages that the longest
-    // sequence would need more splits than the grid has.  Every workgroup derives the same number.
+    // workgroups carry keys whatever the lengths are.  Every workgroup derives the same number.
     int pps = a.pages_per_split;
+    int live_splits = 0, first_item = 0;
     if (adaptive) {
         int sum = len_sum, longest = len_longest;
         if (n_len <= 16) {                       // one length per lane: read the lanes out, add on the scalar side
@@ -617,10 +648,36 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             longest = __builtin_amdgcn_readfirstlane(longest);
         }
         const int sharers = n_len * a.want_splits;
-        const int share = ((sum + sharers - 1) / sharers + 3) & ~3;
-        const int fit = ((longest + a.n_splits - 1) / a.n_splits + 3) & ~3;
-        pps = share > fit ? share : fit;
+        pps = ((sum + sharers - 1) / sharers + 3) & ~3;
+        if (!compact) {                          // the grid has a.n_splits split indices per sequence: the longest must fit
+            const int fit = ((longest + a.n_splits - 1) / a.n_splits + 3) & ~3;
+            pps = pps > fit ? pps : fit;
+        }
         pps = pps > kMinAdaptivePages ? pps : kMinAdaptivePages;
+    }
+    if (compact) {
+        // Items per sequence (lane = sequence; an empty one keeps one item, which writes its zero
+        // rows), then the sequence this workgroup's item falls into.  The items of all sequences
+        // number at most B * (want_splits + 1), the grid's size; the grid's last ones may be spare.
+        int items_lane = (len_sum + pps - 1) / pps;
+        items_lane = lane < n_len ? (items_lane > 0 ? items_lane : 1) : 0;
+        int found = -1, before = 0;
+        for (int i = 0; i < n_len; ++i) {
+            const int n = __builtin_amdgcn_readlane(items_lane, i);
+            if (found < 0 && item < before + n) {
+                found = i;
+                first_item = before;
+                live_splits = n;
+            }
+            before += found < 0 ? n : 0;
+        }
+        if (found < 0) return;                   // a spare item
+        b = found;
+        split = item - first_item;
+        if (b != guessed_b) {                    // another sequence than guessed: its length, queries and key counts
+            len_raw = __builtin_amdgcn_readlane(lens_lane, b);
+            sequence_setup();
+        }
     }
     const int page_lo = split * pps;
     const int my_first = page_lo + wave;
@@ -629,12 +686,14 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     const int my_pages = my_first < page_hi ? (page_hi - my_first + kWaves - 1) / kWaves : 0;
     // Splits that hold keys for this (sequence, column group).  Workgroups past them leave at
     // once; if there is at most one, split 0 writes the output itself and no state is published.
-    const int live_splits = (pages_total + pps - 1) / pps;
-    if (split > 0 && split >= live_splits) return;
+    if (!compact) {
+        live_splits = (pages_total + pps - 1) / pps;
+        if (split > 0 && split >= live_splits) return;
+    }
     // Where nothing was guessed, or the lengths moved this split, its own first pages are loaded (a split
     // that starts where it was guessed to has the same first pages: neither size is below
     // kPrefetch pages per wavefront, so only the sequence's end can cut them short).
-    if (!guess_early || my_first != guessed_first) {
+    if (!guess_early || my_first != guessed_first || b != guessed_b) {
 #pragma unroll
         for (int j = 0; j < kPrefetch; ++j)
             if (j < my_pages)
@@ -766,7 +825,9 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
                 const float inv = lt > 0.f ? 1.f / lt : 0.f;
                 *reinterpret_cast<floatx4*>(a.out + row * D + d4) = acc * inv;
             } else {
-                float* part = a.partials + (row * a.n_splits + split) * (size_t)(D + 2);
+                // one record per (row, split); a launch that numbers its items itself: per (item, head)
+                const size_t rec = compact ? (size_t)item * st.Hq + g * group + hc : row * a.n_splits + split;
+                float* part = a.partials + rec * (size_t)(D + 2);
                 // (D + 2) floats per record keeps 8-byte alignment only: store as pairs
                 publish_pair(part + d4, acc[0], acc[1]);
                 publish_pair(part + d4 + 2, acc[2], acc[3]);
@@ -776,9 +837,12 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     }
     if (live_splits <= 1) return;
 
-    const int n_col_groups = gridDim.z / a.n_splits;
+    const int n_col_groups = compact ? 1 : gridDim.z / a.n_splits;
     if (!arrived_last(a.counters + ((size_t)b * st.Hkv + g) * n_col_groups + cgrp, live_splits)) return;
-    merge_splits<D>(a, b, g, cgrp * NT * 16, NT * 16, ncols, group, live_splits, kThreads);
+    if (compact)       // the records of this sequence's items: first_item .., one head apart per row
+        merge_splits<D>(a, b, g, 0, 16, ncols, group, live_splits, kThreads, 1, st.Hq, ((size_t)first_item - b) * st.Hq);
+    else
+        merge_splits<D>(a, b, g, cgrp * NT * 16, NT * 16, ncols, group, live_splits, kThreads, a.n_splits, 1, 0);
 }
 
 // ------------------------------------------------------------------ wide prefill
@@ -1118,7 +1182,7 @@ void attn_bf16_wide_kernel(AttnArgs a)
     }
     if (live_splits <= 1) return;
     if (!arrived_last(a.counters + ((size_t)b * st.Hkv + g) * n_cblk + cblk, live_splits)) return;
-    merge_splits<D>(a, b, g, cblk * kWideCols, kWideCols, ncols, group, live_splits, kWideThreads);
+    merge_splits<D>(a, b, g, cblk * kWideCols, kWideCols, ncols, group, live_splits, kWideThreads, a.n_splits, 1, 0);
 }
 
 template <int D, bool kFp8>
@@ -1127,6 +1191,7 @@ int launch_bf16(const AttnArgs& a, hipStream_t s)
     const int group = a.st.Hq / a.st.Hkv;
     if (a.T_new == 1) {
         dim3 grid(a.st.Hkv, a.B, a.n_splits);
+        if (a.adaptive == 2) grid = dim3(a.st.Hkv, a.n_items, 1);      // the kernel numbers its work items itself
         hipLaunchKernelGGL((attn_bf16_kernel<D, 1, 4, kFp8>), grid, dim3(kThreads), 0, s, a);
     } else if (a.wide_cols == 256) {
         // Shared-page kernels (the host chose the shape by the number of columns per (sequence, kv

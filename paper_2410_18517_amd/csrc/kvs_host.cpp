@@ -128,22 +128,23 @@ kvs::StoreView view_of(const kvs_store* s, int layer)
 // Query columns (row, head-in-group pairs) one workgroup of the bf16 kernel covers.
 int columns_per_workgroup(int T_new) { return T_new > 1 ? 64 : 16; }
 
-struct Split { int pages_per_split, n_splits, n_col_groups, wide_cols, adaptive, want_splits; };
+struct Split { int pages_per_split, n_splits, n_col_groups, wide_cols, adaptive, want_splits, n_items; };
 
 // A decode launch sizes the page range of a split on the device, by the lengths it finds there
-// (the host never sees them); the host only fixes how many split indices the grid carries: this
-// many times what a batch of full sequences needs.  More than 1 would let a sequence longer than
-// the batch's mean take more workgroups than a shorter one; measured, that gains nothing on mixed
-// lengths and costs the full store the start-up of the workgroups that only leave.
+// (the host never sees them).  Where the grid keeps one split index per (sequence, split) -- per-
+// head lengths -- it carries this many times the indices a batch of full sequences needs.  More
+// than 1 would let a sequence longer than the batch's mean take more workgroups than a shorter
+// one; measured, the workgroups that only leave cost more than that gains.
 constexpr int kSplitHeadroom = 1;
 
-Split choose_split(const kvs_desc* d, int B, int T_new)
+Split choose_split(const kvs_desc* d, int B, int T_new, bool per_head_lens = false)
 {
     Split s;
     const int max_pages = d->max_blocks_per_seq;
     s.wide_cols = 0;
     s.adaptive = 0;
     s.want_splits = 1;
+    s.n_items = 0;
     if (d->dtype == KVS_F32) {           // the fp32 kernel walks the whole context in one wave
         s.pages_per_split = max_pages;
         s.n_splits = 1;
@@ -180,6 +181,17 @@ Split choose_split(const kvs_desc* d, int B, int T_new)
     // (with more than two workgroups per compute unit the order in which they are handed out evens
     // out unequal lengths by itself, and every workgroup would scan that many more lengths)
     if (T_new == 1 && forced == 0 && items <= 2 * kTargetWorkgroups) {
+        if (!per_head_lens && B <= 64 && want > 1) {
+            // One length per sequence, few sequences: the kernel also numbers its work items itself,
+            // every sequence as many as its length asks for.  With pages per split >= all pages /
+            // (B * want) the items number at most B * (want + 1), whatever the lengths.  (Not where
+            // every (sequence, kv head) already has a compute unit to itself, want == 1: cutting the
+            // longer sequences in two there only doubles workgroups up on some units.)
+            s.adaptive = 2;
+            s.want_splits = (int)want;
+            s.n_items = B * ((int)want + 1);
+            return s;
+        }
         const int spare = (int)std::min(most, kSplitHeadroom * want);
         if (spare > 1) {
             s.adaptive = 1;
@@ -200,6 +212,7 @@ size_t counter_bytes(const kvs_desc* d, int B, const Split& s)
 
 size_t partial_floats(const kvs_desc* d, int B, int T_new, const Split& s)
 {
+    if (s.adaptive == 2) return (size_t)s.n_items * d->Hq * (size_t)(d->head_dim + 2);   // a record per (item, query head)
     if (s.n_splits <= 1) return 0;
     return (size_t)B * T_new * d->Hq * s.n_splits * (size_t)(d->head_dim + 2);
 }
@@ -296,8 +309,12 @@ size_t kvs_workspace_bytes(const kvs_desc* d, int B, int max_q_rows)
     const int last = (int)std::min<long>(max_q_rows, capacity);
     const int group = d->Hq / d->Hkv;
     auto need_for = [&](int r) {
-        const Split s = choose_split(d, B, r);
-        return counter_bytes(d, B, s) + partial_floats(d, B, r, s) * sizeof(float);
+        size_t n = 0;
+        for (bool per_head : {false, true}) {          // a decode call may bring either kind of lengths
+            const Split s = choose_split(d, B, r, per_head);
+            n = std::max(n, counter_bytes(d, B, s) + partial_floats(d, B, r, s) * sizeof(float));
+        }
+        return n;
     };
     size_t need = need_for(last);
     if (g_split_tokens.load() > 0 || d->dtype == KVS_F32) return std::max(need, need_for(1));
@@ -457,7 +474,7 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
         return fail(KVS_ERR_CAPACITY, "T_new=%d exceeds the per-sequence capacity", T_new);
     if (!store->block_table && (long)B * d->max_blocks_per_seq > d->num_blocks)
         return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
-    const Split s = choose_split(d, B, T_new);
+    const Split s = choose_split(d, B, T_new, lens_per_head != 0);
     if (B > 65535 || (long)s.n_splits * s.n_col_groups > 65535)
         return fail(KVS_ERR_CAPACITY, "launch too large: B and splits x column groups are limited to 65535");
     const size_t need = counter_bytes(d, B, s) + partial_floats(d, B, T_new, s) * sizeof(float);
@@ -481,6 +498,7 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     a.wide_cols = s.wide_cols;
     a.adaptive = s.adaptive;
     a.want_splits = s.want_splits;
+    a.n_items = s.n_items;
     if (int e = kvs::launch_attention(a, stream)) return fail(KVS_ERR_HIP, "attention launch: %s", kvs::hip_error_string(e));
     return KVS_OK;
 }

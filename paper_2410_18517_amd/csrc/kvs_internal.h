@@ -27,8 +27,10 @@ struct AttnArgs {
     float* partials;        // device fp32 [B][T_new][Hq][n_splits][D + 2]
     int32_t* counters;      // device [B][Hkv][n_col_groups], zero between calls
     int32_t pages_per_split, n_splits;   // n_splits: split indices in the grid and records per row in partials
-    int32_t adaptive;       // decode: the kernel sizes the splits by the lengths it finds (pages_per_split is then what
-    int32_t want_splits;    //   full sequences get); want_splits: workgroups a sequence of mean length is shared among
+    int32_t adaptive;       // decode: 1 = the kernel sizes the splits by the lengths it finds (pages_per_split is then what
+    int32_t want_splits;    //   full sequences get); want_splits: workgroups a sequence of mean length is shared among.
+    int32_t n_items;        //   2 = it also numbers its work items itself: grid (Hkv, n_items), partials one record per
+                            //   (item, query head), n_splits = the splits of a full sequence
     int32_t wide_cols;      // prefill: 0 = the page-splitting kernel, else columns per workgroup of the shared-page kernel (64, 128, 256)
 };
 

@@ -115,9 +115,10 @@ def test_many_splits_merge_is_exact_and_repeatable(kb):
 # for full sequences would put them.  The plain call, the per-head lengths of a sparsified slot
 # (each head of a sequence its own length) and the one-launch decode step all take that path.
 @pytest.mark.parametrize("dtype", ["bf16", "fp8"])
-@pytest.mark.parametrize("kind", ["spread", "short", "one_long"])
-def test_decode_splits_follow_the_lengths(kb, dtype, kind):
-    L, Hq, Hkv, d, B, cap = 2, 16, 8, 128, 16, 2048
+@pytest.mark.parametrize("kind", ["spread", "short", "one_long", "long_last"])
+@pytest.mark.parametrize("Hq,Hkv,B", [(16, 8, 16), (4, 2, 40)])      # up to 16 sequences: lengths read out of the lanes
+def test_decode_splits_follow_the_lengths(kb, dtype, kind, Hq, Hkv, B):
+    L, d, cap = 2, 128, 2048
     share = np.array([0, 0], np.int32)
     case = Case(kb, L, Hq, Hkv, d, B, dtype, cap, share, paged=True, seed=97)
     rng = np.random.default_rng(97)
@@ -128,7 +129,7 @@ def test_decode_splits_follow_the_lengths(kb, dtype, kind):
         lens = rng.integers(480, 520, size=B).astype(np.int32)
     else:
         lens = np.full(B, 40, np.int32)
-        lens[5] = cap
+        lens[5 if kind == "one_long" else B - 1] = cap
     q = case.q(1)
     qo = inputs.to_oracle_array(q)
     for _ in range(2):                                             # twice: counters are left at zero
