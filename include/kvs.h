@@ -197,10 +197,11 @@ int kvs_decode_attention(const kvs_store* store, int layer, const void* q,
  * One decode step in one launch: kvs_append_kv(k_new, v_new at position seq_lens[b] - 1) followed
  * by kvs_decode_attention(q, seq_lens), for the layers that keep their own cache; for a layer
  * that reads a donor's cache k_new and v_new are ignored and the call is kvs_decode_attention
- * (its donor stored this step's token when its own turn came).  On a bf16 store the attention
- * kernel takes the new token from k_new / v_new directly -- it joins the softmax in the merge of
- * the context splits -- and writes it to its place in the store on the side, so no second launch
- * and no wait for the write; on other store types the call is the two launches.
+ * (its donor stored this step's token when its own turn came).  On a bf16 or fp8 store the
+ * attention kernel takes the new token from k_new / v_new directly -- it joins the softmax in the
+ * merge of the context splits, with the values the store will hold (rounded to E4M3 for an fp8
+ * store) -- and writes it to its place in the store on the side, so no second launch and no wait
+ * for the write; on an fp32 store the call is the two launches.
  *   q device [B][Hq][head_dim], k_new, v_new device [B][1][Hkv][head_dim], all bf16 (fp32 for an
  *   fp32 store);  seq_lens device [B], counting the new token;  out, workspace as
  *   kvs_decode_attention.  Positions at or beyond the capacity are not stored.

@@ -529,7 +529,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
     // all of them, in the same round trip as the look-ups above, and derives the same pages per
     // split further down.  lens_lane: what the length array holds for sequence `lane` (compact
     // launches have at most 64 sequences).
-    const bool carries_new = NT == 1 && !kFp8 && a.k_new != nullptr;
+    const bool carries_new = NT == 1 && a.k_new != nullptr;
     const bool adaptive = NT == 1 && a.adaptive;
     const int n_len = a.lens_per_head ? a.B * st.Hkv : a.B;
     int len_sum = 0, len_longest = 0;             // in pages, this lane's share of the lengths
@@ -747,19 +747,41 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
 
     __shared__ float lds_new_score[16];               // log2-domain score of the step's own token, per column
     const bool adds_new = has_new && split == 0;
+    // the new row as the store will hold it: as given (bf16 store), rounded to E4M3 (fp8 store)
+    auto as_stored = [](unsigned short h) -> float {
+        const unsigned w = kFp8 ? e4m3_to_bf16(bf16_to_e4m3(h)) : h;
+        return __uint_as_float(w << 16);
+    };
     if (adds_new) {
         const unsigned short* k_row = static_cast<const unsigned short*>(a.k_new) + ((size_t)b * st.Hkv + g) * D;
         const unsigned short* v_row = static_cast<const unsigned short*>(a.v_new) + ((size_t)b * st.Hkv + g) * D;
         // its place in the store, for the steps to come (this launch masks that position)
         const int blk = block_of(st, b, new_pos / kPageTokens);
         if (blk >= 0 && blk < st.num_blocks) {
-            unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, slot, blk, g);
-            unsigned short* vp = kp + kPageTokens * D;
             const int t = new_pos % kPageTokens;
-            if ((int)threadIdx.x < D / 8)
-                *reinterpret_cast<uint4*>(kp + k_index_bf16(t, threadIdx.x * 8)) =
-                    *reinterpret_cast<const uint4*>(k_row + threadIdx.x * 8);
-            if ((int)threadIdx.x < D) vp[v_index_bf16(t, threadIdx.x)] = v_row[threadIdx.x];
+            if constexpr (kFp8) {
+                unsigned char* kp = static_cast<unsigned char*>(st.pool) + page_offset(st, slot, blk, g);
+                unsigned char* vp = kp + kPageTokens * D;
+                if ((int)threadIdx.x < D / 8) {
+                    const uint4 w = *reinterpret_cast<const uint4*>(k_row + threadIdx.x * 8);
+                    const unsigned kw[4] = {w.x, w.y, w.z, w.w};
+                    unsigned lo = 0, hi = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        lo |= bf16_to_e4m3((kw[e >> 1] >> ((e & 1) * 16)) & 0xffffu) << (8 * e);
+                        hi |= bf16_to_e4m3((kw[2 + (e >> 1)] >> ((e & 1) * 16)) & 0xffffu) << (8 * e);
+                    }
+                    *reinterpret_cast<uint2*>(kp + k_index_fp8(t, threadIdx.x * 8)) = make_uint2(lo, hi);
+                }
+                if ((int)threadIdx.x < D) vp[v_index_fp8(t, threadIdx.x)] = (unsigned char)bf16_to_e4m3(v_row[threadIdx.x]);
+            } else {
+                unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, slot, blk, g);
+                unsigned short* vp = kp + kPageTokens * D;
+                if ((int)threadIdx.x < D / 8)
+                    *reinterpret_cast<uint4*>(kp + k_index_bf16(t, threadIdx.x * 8)) =
+                        *reinterpret_cast<const uint4*>(k_row + threadIdx.x * 8);
+                if ((int)threadIdx.x < D) vp[v_index_bf16(t, threadIdx.x)] = v_row[threadIdx.x];
+            }
         }
         // q . k_new for the 16 columns: a wavefront takes four columns, sixteen lanes each
         constexpr int CH = D / 16;
@@ -769,7 +791,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             const unsigned short* qr = qbase + (((size_t)b * a.T_new) * st.Hq + g * group + cc) * D + part * CH;
 #pragma unroll
             for (int e = 0; e < CH; ++e)
-                dot += __uint_as_float((unsigned)qr[e] << 16) * __uint_as_float((unsigned)k_row[part * CH + e] << 16);
+                dot += __uint_as_float((unsigned)qr[e] << 16) * as_stored(k_row[part * CH + e]);
         }
 #pragma unroll
         for (int o_ = 8; o_ > 0; o_ >>= 1) dot += __shfl_xor(dot, o_);
@@ -809,8 +831,7 @@ __global__ __launch_bounds__(kThreads) void attn_bf16_kernel(AttnArgs a)
             if (adds_new) {                                   // weight 2^(score - M), value row v_new
                 const unsigned short* v_row = static_cast<const unsigned short*>(a.v_new) + ((size_t)b * st.Hkv + g) * D + d4;
                 const float wgt = __builtin_amdgcn_exp2f(m_new_tok - M_use);
-                acc = wgt * floatx4{__uint_as_float((unsigned)v_row[0] << 16), __uint_as_float((unsigned)v_row[1] << 16),
-                                    __uint_as_float((unsigned)v_row[2] << 16), __uint_as_float((unsigned)v_row[3] << 16)};
+                acc = wgt * floatx4{as_stored(v_row[0]), as_stored(v_row[1]), as_stored(v_row[2]), as_stored(v_row[3])};
                 lt = wgt;
             }
 #pragma unroll

@@ -516,8 +516,8 @@ int kvs_decode_step(const kvs_store* store, int layer, const void* q, const void
     if (int rc = check_store(store, layer)) return rc;
     if (!k_new || !v_new || !seq_lens) return fail(KVS_ERR_INVALID_ARG, "k_new, v_new or seq_lens is NULL");
     const bool own = store->host_share_map[layer] == layer;
-    if (own && store->desc.dtype != KVS_BF16) {
-        // other store types: the two launches the fused kernel replaces
+    if (own && store->desc.dtype == KVS_F32) {
+        // the fp32 store: the two launches the fused kernel replaces
         if (int rc = append_common(store, layer, k_new, v_new, seq_lens, 0, B, 1, stream, -1)) return rc;
         return attention_common(store, layer, q, seq_lens, 0, 0, B, 1, out, workspace, workspace_bytes, stream);
     }
