@@ -180,7 +180,8 @@ Split choose_split(const kvs_desc* d, int B, int T_new, bool per_head_lens = fal
     s.n_splits = (max_pages + pps - 1) / pps;
     // (with more than two workgroups per compute unit the order in which they are handed out evens
     // out unequal lengths by itself, and every workgroup would scan that many more lengths)
-    if (T_new == 1 && forced == 0 && items <= 2 * kTargetWorkgroups) {
+    // (and the kernel adds up all lengths in pages as 32-bit integers)
+    if (T_new == 1 && forced == 0 && items <= 2 * kTargetWorkgroups && items * max_pages < (1L << 30)) {
         if (!per_head_lens && B <= 64 && want > 1) {
             // One length per sequence, few sequences: the kernel also numbers its work items itself,
             // every sequence as many as its length asks for.  With pages per split >= all pages /
