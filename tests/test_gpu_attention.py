@@ -158,6 +158,39 @@ def test_decode_splits_follow_the_lengths(kb, dtype, kind, Hq, Hkv, B):
     assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
 
 
+# Seeded random shapes and length patterns through the plain decode call: batch sizes on either side
+# of 16 and 64 (how a launch reads the lengths), capacities off a multiple of the split sizes,
+# contiguous and paged stores.
+def test_randomised_decode_lengths(kb):
+    rng = np.random.default_rng(20241018)
+    for case_i in range(16):
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        group = int(rng.choice([1, 2, 4, 6]))
+        d = int(rng.choice([64, 128]))
+        B = int(rng.choice([1, 3, 16, 17, 64, 70]))
+        cap = int(rng.choice([512, 1024, 2048])) + int(rng.choice([0, 16, 48]))
+        dtype = str(rng.choice(["bf16", "fp8"]))
+        kind = str(rng.choice(["uniform", "spread", "one_long", "zeros"]))
+        if kind == "uniform":
+            lens = np.full(B, rng.integers(1, cap + 1))
+        elif kind == "spread":
+            lens = rng.integers(0, cap + 1, size=B)
+        elif kind == "one_long":
+            lens = rng.integers(0, 64, size=B)
+            lens[rng.integers(0, B)] = cap
+        else:
+            lens = np.zeros(B, np.int64)
+            lens[rng.integers(0, B)] = rng.integers(0, cap + 1)
+        lens = lens.astype(np.int32)
+        share = np.array([0, 0], np.int32)
+        case = Case(kb, 2, Hkv * group, Hkv, d, B, dtype, cap, share, paged=bool(rng.integers(0, 2)), seed=300 + case_i)
+        q = case.q(1)
+        got = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens).cpu().numpy()
+        want = orc.decode_attention(1, share, case.K, case.V, inputs.to_oracle_array(q), lens)
+        assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION, (case_i, Hkv, group, d, B, cap, dtype, kind)
+        del case
+
+
 @pytest.mark.parametrize("gain", [0.05, 4.0, 24.0])
 def test_bf16_flat_and_peaked_softmax(kb, gain):
     """Scores from nearly constant to widely spread (the running reference of the exponentials has
