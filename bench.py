@@ -308,6 +308,9 @@ def main():
                     help="decode mode: record the step's launches once into a HIP graph and time its replays")
     ap.add_argument("--store", choices=["fp8"], default=None,
                     help="decode and prefill modes: keep the slots in fp8 (E4M3) instead of the workload's type")
+    ap.add_argument("--seq-lens", default=None,
+                    help="decode mode: comma-separated lengths (tokens, counting this step's), one per sequence, in "
+                         "place of the workload's: a store below its capacity, or one long sequence among short ones")
     ap.add_argument("--prefill-rows", type=int, default=0,
                     help="--mode prefill: rows per sequence in the chunk (default: the workload's 64)")
     ap.add_argument("--project-rows", type=int, default=1,
@@ -344,6 +347,10 @@ def main():
 
     share = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)
     seq_lens = inputs.make_seq_lens(w, 1)
+    if args.seq_lens:
+        seq_lens = np.array([int(x) for x in args.seq_lens.split(",")], np.int32)
+        if len(seq_lens) != w.B or seq_lens.min() < 1 or seq_lens.max() > w.context:
+            sys.exit(f"--seq-lens needs {w.B} lengths in [1, {w.context}]")
     max_blocks = w.max_blocks_per_seq
     num_blocks = w.B * max_blocks
     table = inputs.make_block_table(w.B, max_blocks, num_blocks, 1)
@@ -438,7 +445,8 @@ def main():
                     ", fp8 pages" if store_dtype == "fp8" else ""),
                 "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": recorded_traffic(w.name) if store_dtype == w.dtype else None, "launch_us": round(launch_ms * 1e3, 2),
+                "traffic": recorded_traffic(w.name) if store_dtype == w.dtype and not args.seq_lens else None,
+                "launch_us": round(launch_ms * 1e3, 2),
                 "algorithmic_bytes": alg_bytes}
 
     result = {
@@ -446,7 +454,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name if store_dtype == w.dtype else f"{w.name}, {store_dtype} slots", "layers": w.L, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
-                   "batch": w.B, "context": w.context if w.min_context is None else [w.min_context, w.context],
+                   "batch": w.B, "context": [int(n) for n in seq_lens] if args.seq_lens else
+                   (w.context if w.min_context is None else [w.min_context, w.context]),
+                   "capacity": w.context,
                    "page_tokens": 16, "shared_layers": w.n_shared, "kv_slots": int(store.desc.n_slots),
                    "step": "kvs_append_kv + kvs_decode_attention per layer" if args.two_calls
                            else "kvs_decode_step per layer",
@@ -482,7 +492,7 @@ def main():
         result["cpu_baseline"] = {
             "value": round(w.B / cpu_s, 4), "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": f"fp64 oracle, decode attention of all {w.L} layers of one step (the appends are not "
-                      f"timed), all {w.B} sequences x {w.Hq} heads at full context: {cpu_s:.2f} s"}
+                      f"timed), all {w.B} sequences x {w.Hq} heads at {'the given lengths' if args.seq_lens else 'full context'}: {cpu_s:.2f} s"}
         result["parity_rel_l2_max"] = err
     print(json.dumps(result))
 
