@@ -158,7 +158,7 @@ def bench_distance(args, torch, kb, inputs, dev):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us * 1e-3, 4),
         "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "calibration 30 x 48 layers x (8 x 512 x 128)", "samples": S, "layers": L, "N": N},
-        "roofline": {"bound": "hbm", "kernel": "distance_partial_kernel<bf16> + distance_final_kernel",
+        "roofline": {"bound": "hbm", "kernel": "distance_partial_kernel<bf16, 256-position chunks> + distance_final_kernel",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "launch_us": round(us, 2),
                      "algorithmic_bytes": nbytes}}))

@@ -283,7 +283,7 @@ int kvs_set_split_tokens(int tokens);
  * i.e. the Euclidean distance between the flattened [mean K ; mean V] vectors.  Outputs are
  * device fp32 [L][L], symmetric with a zero diagonal; dK2 and dV2 are returned so that other
  * readings of the paper's separate averaging of keys and values can be formed by the caller.
- * Supported: L <= 64.  workspace >= kvs_distance_workspace_bytes(L).
+ * Supported: L <= 128.  workspace >= kvs_distance_workspace_bytes(L).
  */
 int kvs_layer_distance(const void* kv_samples, int S, int L, size_t N, int dtype,
                        float* dK2, float* dV2, float* D,

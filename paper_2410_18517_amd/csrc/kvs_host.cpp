@@ -548,7 +548,7 @@ int kvs_prefill_attention(const kvs_store* store, int layer, const void* q, cons
 
 size_t kvs_distance_workspace_bytes(int L)
 {
-    if (L <= 0 || L > 64) { fail(KVS_ERR_UNSUPPORTED, "L must be in [1, 64]"); return 0; }
+    if (L <= 0 || L > 128) { fail(KVS_ERR_UNSUPPORTED, "L must be in [1, 128]"); return 0; }
     return kvs::distance_workspace_bytes(L);
 }
 
@@ -558,7 +558,7 @@ int kvs_layer_distance(const void* kv_samples, int S, int L, size_t N, int dtype
 {
     if (!kv_samples || !dK2 || !dV2 || !D) return fail(KVS_ERR_INVALID_ARG, "NULL argument");
     if (S <= 0 || L <= 0 || N == 0) return fail(KVS_ERR_INVALID_ARG, "S, L and N must be positive");
-    if (L > 64) return fail(KVS_ERR_UNSUPPORTED, "L=%d: at most 64 layers are supported", L);
+    if (L > 128) return fail(KVS_ERR_UNSUPPORTED, "L=%d: at most 128 layers are supported", L);
     if (dtype != KVS_F32 && dtype != KVS_BF16) return fail(KVS_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
     if (N % 8 != 0) return fail(KVS_ERR_UNSUPPORTED, "N must be a multiple of 8 (got %zu)", N);
     if ((size_t)S * L * 2 > ((size_t)1 << 62) / N) return fail(KVS_ERR_CAPACITY, "input too large");

@@ -32,7 +32,10 @@ def _compare(kb, kv):
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("S,L,Hkv,T,d", [(1, 2, 1, 1, 8), (3, 5, 2, 7, 8), (30, 48, 2, 16, 64), (4, 64, 1, 33, 8),
-                                          (2, 7, 1, 300, 8)])
+                                          (2, 7, 1, 300, 8),
+                                          # beyond 64 layers (80: the largest model of the paper's appendix): half
+                                          # the chunk, up to two pair blocks per thread
+                                          (5, 65, 2, 16, 64), (7, 80, 1, 37, 8), (3, 128, 1, 21, 8), (30, 80, 8, 8, 128)])
 def test_distance_small(kb, dtype, S, L, Hkv, T, d):
     kv = inputs.calibration_kv(S, L, Hkv, T, d, S * 1000 + L, dtype=dtype)
     _compare(kb, kv)

@@ -107,7 +107,8 @@ def test_store_and_workspace_sizes():
         assert lib.kvs_store_bytes(C.byref(_desc(**bad))) == 0, bad
         assert kb.last_error()
     assert lib.kvs_workspace_bytes(C.byref(d), 0, 1) == 0
-    assert lib.kvs_distance_workspace_bytes(65) == 0 and lib.kvs_distance_workspace_bytes(48) > 0
+    assert lib.kvs_distance_workspace_bytes(129) == 0 and lib.kvs_distance_workspace_bytes(48) > 0
+    assert lib.kvs_distance_workspace_bytes(128) > lib.kvs_distance_workspace_bytes(64)      # per pair block of layers
     # projection: 2*Hkv*(d/32) output tiles per 16 rows, one counter each (padded to 256 bytes), and
     # when the contraction is split, one 256-thread pair of floats per tile and split
     big = _desc(Hq=32, Hkv=8)
@@ -214,7 +215,7 @@ def test_entry_points_reject_bad_arguments_without_touching_the_gpu():
     assert lib.kvs_decode_step(C.byref(st), 0, p, p, p, p, 1, p, None, 0, None) == kb.KVS_ERR_INVALID_ARG
     # distance
     assert lib.kvs_layer_distance(None, 1, 2, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
-    assert lib.kvs_layer_distance(p, 1, 65, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
+    assert lib.kvs_layer_distance(p, 1, 129, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
     assert lib.kvs_layer_distance(p, 1, 2, 12, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
     assert lib.kvs_layer_distance(p, 0, 2, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_layer_distance(p, 1, 2, 8, 0, p, p, p, p, 16, None) == kb.KVS_ERR_INVALID_ARG
