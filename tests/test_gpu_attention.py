@@ -405,6 +405,29 @@ def test_shared_page_prefill_rising_scores(kb, Hq, Hkv, B, T_new):
             assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, (gain, b)
 
 
+def test_deep_model_layers_beyond_the_first_look_up(kb):
+    """80 layers (the paper's largest model): the kernel's first look-up carries the slots of layers
+    0..55 only, so a layer whose donor lies beyond them resolves its slot with a second look-up."""
+    L, Hq, Hkv, d, B, cap = 80, 16, 2, 128, 2, 80
+    share = np.arange(L, dtype=np.int32)
+    share[79], share[70], share[57] = 60, 3, 56
+    for dtype in ("bf16", "fp8", "f32"):
+        case = Case(kb, L, Hq if dtype != "f32" else 4, Hkv, d if dtype != "f32" else 64, B, dtype, cap, share, seed=61,
+                    fill_layers=[3, 56, 60, 78])
+        lens = np.array([cap, 37], np.int32)
+        tol = 1e-5 if dtype == "f32" else REL_L2_ATTENTION
+        for layer in (79, 70, 57, 78, 60, 3):
+            q = case.q(layer)
+            got = kb.kvs_decode_attention(case.store, layer, q.cuda(), lens).cpu().numpy()
+            want = orc.decode_attention(layer, share, case.K, case.V, inputs.to_oracle_array(q), lens)
+            assert rel_l2_rows(got, want).max() <= tol, (dtype, layer)
+        q = case.q(79, rows=20)
+        start = np.array([cap - 20, 3], np.int32)
+        got = kb.kvs_prefill_attention(case.store, 79, q.cuda(), start).cpu().numpy()
+        want = orc.shared_attention(79, share, case.K, case.V, inputs.to_oracle_array(q), start)
+        assert rel_l2_rows(got, want).max() <= tol, (dtype, "prefill")
+
+
 def test_randomised_shapes_maps_and_lengths(kb):
     """Seeded sweep over store types, head groupings, batch sizes, sharing maps, paging, split sizes
     and ragged lengths; every case is compared element by element with the oracle."""
