@@ -75,8 +75,8 @@ __device__ __forceinline__ void sum_samples_f32(const float* row0, size_t stride
     }
 }
 
-// kPer: pair blocks per thread (1 while the 4 x 4 blocks of the upper triangle number at most
-// kThreads, i.e. up to 124 layers... 2 beyond 64 layers, where the chunk is halved as well).
+// kPer: pair blocks per thread: 1 while the 4 x 4 blocks of the upper triangle number at most
+// kThreads (up to 124 layers), 2 beyond.
 template <bool kBf16, int kChunk, int kPer>
 __global__ __launch_bounds__(kThreads) void distance_partial_kernel(const void* kv, int S, int L, size_t N,
                                                                     int chunks_per_wg, float* partial)
@@ -238,7 +238,7 @@ int blocks_for(int L)
 size_t lds_bytes(int L)
 {
     const size_t means = (size_t)L * chunk_for(L) * sizeof(float);
-    const size_t fold = (size_t)(L <= 64 ? 1 : 2) * kThreads * kAccPerThread * sizeof(float);
+    const size_t fold = (size_t)(blocks_for(L) <= kThreads ? 1 : 2) * kThreads * kAccPerThread * sizeof(float);
     return means > fold ? means : fold;
 }
 
@@ -292,6 +292,9 @@ int launch_layer_distance(const void* kv, int S, int L, size_t N, int dtype, flo
     int n_wg = 0, e;
     if (L <= 64) e = dtype == 1 ? launch_partial<true, 256, 1>(kv, S, L, N, partial, &n_wg, s)
                                 : launch_partial<false, 256, 1>(kv, S, L, N, partial, &n_wg, s);
+    else if (blocks_for(L) <= kThreads)          // up to 124 layers: still one pair block per thread
+        e = dtype == 1 ? launch_partial<true, 128, 1>(kv, S, L, N, partial, &n_wg, s)
+                       : launch_partial<false, 128, 1>(kv, S, L, N, partial, &n_wg, s);
     else e = dtype == 1 ? launch_partial<true, 128, 2>(kv, S, L, N, partial, &n_wg, s)
                         : launch_partial<false, 128, 2>(kv, S, L, N, partial, &n_wg, s);
     if (e) return e;
