@@ -78,7 +78,8 @@ __device__ __forceinline__ void sum_samples_f32(const float* row0, size_t stride
 // kPer: pair blocks per thread: 1 while the 4 x 4 blocks of the upper triangle number at most
 // kThreads (up to 124 layers), 2 beyond.
 template <bool kBf16, int kChunk, int kPer>
-__global__ __launch_bounds__(kThreads) void distance_partial_kernel(const void* kv, int S, int L, size_t N,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4)))
+void distance_partial_kernel(const void* kv, int S, int L, size_t N,
                                                                     int chunks_per_wg, float* partial)
 {
     extern __shared__ float lds[];                      // means [L][kChunk] (rotated rows); reused at the end
