@@ -89,7 +89,7 @@ typedef int (*kvs_accept_fn)(const int32_t* candidate_share_map, int L, void* us
  *   share_map, slot_of_layer   host, out[L];  n_slots, n_shared   host, out
  * Returns KVS_OK, or KVS_ERR_TARGET_UNREACHED with the partial strategy in the outputs
  * when the ranking is exhausted first (the search then reports that it found no strategy).
- * The random-sharing baseline (Sec. 5.2, random pairs at a fixed compression rate) is the same
+ * The random-sharing baseline (Sec. 5.3, random pairs at a fixed compression rate) is the same
  * walk over a ranking drawn at random: pass a matrix of independent random values, accept = NULL.
  */
 int kvs_build_share_map(const float* dist, int L, int target_shared, int order,
@@ -132,9 +132,13 @@ typedef struct kvs_store {
 size_t kvs_store_bytes(const kvs_desc* desc);
 
 /* Bytes of scratch the attention calls need for B sequences of 1 to max_q_rows query rows
- * each (1 for decode): enough for every row count in that range.  The scratch holds split-context partial results and per-(sequence,
- * kv head) arrival counters; the caller zero-fills it once after allocating it, and every
- * call leaves the counters zero again.  Calls sharing one workspace must not overlap. */
+ * each (1 for decode): enough for every row count in that range.  The scratch starts with a
+ * region of arrival counters whose size is the same for every call (64 KiB), followed by the
+ * split-context partial results.  The caller zero-fills the workspace once after allocating it;
+ * every call leaves the counters zero again and writes partial results only behind the counter
+ * region, so calls of different batch sizes, row counts and kinds (decode, prefill, per-head) may
+ * take turns on one workspace that is large enough for each of them.  Calls sharing one
+ * workspace must not overlap in time. */
 size_t kvs_workspace_bytes(const kvs_desc* desc, int B, int max_q_rows);
 
 /*
@@ -159,9 +163,10 @@ int kvs_append_kv(const kvs_store* store, int layer, const void* k_new, const vo
  *     rounds that bf16 value on to E4M3, as kvs_append_kv of the bf16 row would).
  * rope_cos, rope_sin: device fp32 [rope_positions][head_dim/2], rope_positions >= capacity.
  * bf16 and fp8 stores (x and the weights are bf16 either way); hidden a multiple of 128.  workspace: device, >=
- * kvs_project_workspace_bytes(), zero-filled once by the caller and left zero by every call
- * (it holds arrival counters and partial sums of the split contraction); calls sharing it must
- * not overlap.  Returns KVS_NOOP without touching the GPU when the layer reads a donor's cache.
+ * kvs_project_workspace_bytes(), zero-filled once by the caller; it has the layout of the attention
+ * workspace (a 64 KiB region of arrival counters that every call leaves zero, then the partial sums
+ * of the split contraction), so calls of any row count may take turns on it; calls sharing it must
+ * not overlap in time.  Returns KVS_NOOP without touching the GPU when the layer reads a donor's cache.
  */
 int kvs_project_append_kv(const kvs_store* store, int layer, const void* x, int hidden,
                           const void* w_k, const void* w_v,
@@ -179,6 +184,19 @@ size_t kvs_project_workspace_bytes(const kvs_desc* desc, int hidden, int B, int 
  */
 int kvs_gather_kv(const kvs_store* store, int layer, int t0, int T, int B,
                   void* k_out, void* v_out, void* stream);
+
+/*
+ * Debug aid for the share-map and page indexing of Sec. 3.2.  The kernels resolve
+ * slot_of_layer[share_map[layer]] and the pages from the store's DEVICE arrays and clamp whatever
+ * they find into the pool (memory safety), while argument checks and the KVS_NOOP decisions use
+ * the HOST copies: the two must hold the same values, and a difference, or a page-table entry
+ * outside [0, num_blocks), is otherwise silent (the call reads or writes some other slot or page
+ * and returns KVS_OK).  This call makes it observable: report (device int32[2]) receives
+ *   report[0] = entries of share_map / slot_of_layer whose device value differs from the host copy,
+ *   report[1] = entries of the first B rows of the block table outside [0, num_blocks)
+ * (0 for a contiguous store).  One small kernel on `stream`; L <= 256.
+ */
+int kvs_check_store(const kvs_store* store, int B, int32_t* report, void* stream);
 
 /*
  * One decode step of `layer` (Sec. 3.2): out[b][h][:] = softmax_j(q[b][h] . K[b][g][j] /
@@ -267,10 +285,6 @@ int kvs_append_kv_per_head(const kvs_store* store, int layer, const void* k_new,
 int kvs_decode_attention_per_head(const kvs_store* store, int layer, const void* q,
                                   const int32_t* kv_lens, int B, float* out,
                                   void* workspace, size_t workspace_bytes, void* stream);
-
-/* Context tokens handled by one workgroup of the split-context decode kernel; 0 restores the
- * built-in choice.  Must be a multiple of 64.  Process-wide; for tuning and tests. */
-int kvs_set_split_tokens(int tokens);
 
 /* ---------------------------------------------------------------- calibration distance */
 

@@ -1,0 +1,27 @@
+/*
+ * kvs_testing.h -- hooks of libkvs for its own tests and for tuning runs.  Not part of the
+ * interface a serving stack builds on: nothing here is needed to use the library, and what is
+ * here is process-wide state.
+ */
+#ifndef KVS_TESTING_H
+#define KVS_TESTING_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Force the number of context tokens one workgroup of the split-context attention kernels
+ * handles (a multiple of 64), so that small test cases run through many splits and their merge;
+ * 0 restores the built-in choice, which sizes the splits to fill the GPU.  The setting is
+ * process-wide and read by every later kvs_workspace_bytes() and attention call on every store
+ * and thread: after changing it, query the workspace size again (a workspace sized under
+ * another setting may be refused as too small; its contents stay valid, the counter region at
+ * its start does not move).  Returns KVS_OK or KVS_ERR_INVALID_ARG.
+ */
+int kvs_testing_force_split_tokens(int tokens);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVS_TESTING_H */

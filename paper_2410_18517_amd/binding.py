@@ -22,10 +22,11 @@ KVS_BLOCK_TOKENS = 16
 EXPORTS = [
     "kvs_last_error", "kvs_build_share_map", "kvs_validate_share_map", "kvs_slots_from_share_map",
     "kvs_store_bytes", "kvs_workspace_bytes", "kvs_append_kv", "kvs_gather_kv",
-    "kvs_decode_attention", "kvs_prefill_attention", "kvs_set_split_tokens",
+    "kvs_decode_attention", "kvs_prefill_attention", "kvs_testing_force_split_tokens",
     "kvs_layer_distance", "kvs_distance_workspace_bytes", "kvs_avg_cos_sim", "kvs_cos_sim_workspace_bytes",
     "kvs_project_append_kv", "kvs_project_workspace_bytes",
     "kvs_compact_kv", "kvs_append_kv_per_head", "kvs_decode_attention_per_head", "kvs_decode_step",
+    "kvs_check_store",
 ]
 
 
@@ -83,7 +84,8 @@ def lib():
                                       C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvs_prefill_attention.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                             C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-        L.kvs_set_split_tokens.argtypes = [C.c_int]
+        L.kvs_testing_force_split_tokens.argtypes = [C.c_int]
+        L.kvs_check_store.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p]
         L.kvs_layer_distance.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_size_t, C.c_int, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvs_project_append_kv.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
@@ -151,8 +153,8 @@ def kvs_slots_from_share_map(share_map):
     return slot, n.value
 
 
-def kvs_set_split_tokens(tokens: int):
-    _check(lib().kvs_set_split_tokens(int(tokens)))
+def kvs_testing_force_split_tokens(tokens: int):
+    _check(lib().kvs_testing_force_split_tokens(int(tokens)))
 
 
 # ------------------------------------------------------------------ store
@@ -275,6 +277,13 @@ def kvs_project_append_kv(store: KVStore, layer, x, w_k, w_v, start_pos, rope_co
         rope_cos.data_ptr() if rope_cos is not None else None,
         rope_sin.data_ptr() if rope_sin is not None else None, int(positions),
         sp.data_ptr(), int(B), int(T_new), workspace.data_ptr(), workspace.numel(), _stream()), ok=(KVS_OK, KVS_NOOP))
+
+
+def kvs_check_store(store: KVStore, B):
+    """Device tensor int32 [2]: (map entries that differ from the host copies, page-table entries out of range)."""
+    report = torch.empty(2, dtype=torch.int32, device=store.device)
+    _check(lib().kvs_check_store(C.byref(store.c), int(B), report.data_ptr(), _stream()))
+    return report
 
 
 def kvs_gather_kv(store: KVStore, layer, t0, T, B):

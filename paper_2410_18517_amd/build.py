@@ -20,7 +20,7 @@ def is_stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     deps = sources() + [os.path.join(CSRC, "kvs_internal.h"), os.path.join(CSRC, "kvs_device.h"),
-                        os.path.join(HERE, "..", "include", "kvs.h")]
+                        os.path.join(HERE, "..", "include", "kvs.h"), os.path.join(HERE, "..", "include", "kvs_testing.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

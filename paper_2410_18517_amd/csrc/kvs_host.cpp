@@ -1,6 +1,7 @@
 // Host side of libkvs: argument checks, the strategy-search walk, launch geometry.
 // Everything that can be decided without the GPU is decided here, before any HIP call.
 #include "../../include/kvs.h"
+#include "../../include/kvs_testing.h"
 #include "kvs_internal.h"
 
 #include <algorithm>
@@ -203,12 +204,14 @@ Split choose_split(const kvs_desc* d, int B, int T_new, bool per_head_lens = fal
     return s;
 }
 
-// Workspace layout: arrival counters first (they must start, and are left, at zero), then
-// the per-split partial states.
-size_t counter_bytes(const kvs_desc* d, int B, const Split& s)
+// Workspace layout: the counter region (fixed size, so that calls of any shape agree on where it
+// ends), then the per-split partial states.  Counters are indexed by (sequence, kv head, column
+// group) and are touched only by calls that split the context; the built-in policy splits only
+// while those items are fewer than the workgroups it aims for, far below the region's capacity.
+size_t counters_used(const kvs_desc* d, int B, const Split& s)
 {
-    const size_t n = (size_t)B * d->Hkv * s.n_col_groups * sizeof(int32_t);
-    return (n + 255) / 256 * 256;
+    if (s.n_splits <= 1 && !s.adaptive) return 0;
+    return (size_t)B * d->Hkv * s.n_col_groups;
 }
 
 size_t partial_floats(const kvs_desc* d, int B, int T_new, const Split& s)
@@ -291,7 +294,7 @@ size_t kvs_store_bytes(const kvs_desc* d)
            elem_bytes(d->dtype);
 }
 
-int kvs_set_split_tokens(int tokens)
+int kvs_testing_force_split_tokens(int tokens)
 {
     if (tokens < 0 || tokens % 64 != 0) return fail(KVS_ERR_INVALID_ARG, "split tokens must be 0 or a multiple of 64");
     g_split_tokens.store(tokens);
@@ -313,7 +316,7 @@ size_t kvs_workspace_bytes(const kvs_desc* d, int B, int max_q_rows)
         size_t n = 0;
         for (bool per_head : {false, true}) {          // a decode call may bring either kind of lengths
             const Split s = choose_split(d, B, r, per_head);
-            n = std::max(n, counter_bytes(d, B, s) + partial_floats(d, B, r, s) * sizeof(float));
+            n = std::max(n, kvs::kCounterRegionBytes + partial_floats(d, B, r, s) * sizeof(float));
         }
         return n;
     };
@@ -462,6 +465,25 @@ int kvs_gather_kv(const kvs_store* store, int layer, int t0, int T, int B,
     return KVS_OK;
 }
 
+int kvs_check_store(const kvs_store* store, int B, int32_t* report, void* stream)
+{
+    if (int rc = check_store(store, 0)) return rc;
+    if (!report) return fail(KVS_ERR_INVALID_ARG, "report is NULL");
+    if (B < 0) return fail(KVS_ERR_INVALID_ARG, "B must not be negative (B=%d)", B);
+    if (store->desc.L > kvs::kMaxCheckedLayers)
+        return fail(KVS_ERR_UNSUPPORTED, "the check covers at most %d layers (L=%d)", kvs::kMaxCheckedLayers, store->desc.L);
+    if (!store->block_table && (long)B * store->desc.max_blocks_per_seq > store->desc.num_blocks)
+        return fail(KVS_ERR_CAPACITY, "contiguous store: B * max_blocks_per_seq exceeds num_blocks");
+    kvs::CheckArgs a = {};
+    a.st = view_of(store, 0);
+    a.B = B;
+    a.report = report;
+    std::copy(store->host_share_map, store->host_share_map + store->desc.L, a.host_share_map);
+    std::copy(store->host_slot_of_layer, store->host_slot_of_layer + store->desc.L, a.host_slot_of_layer);
+    if (int e = kvs::launch_check_store(a, stream)) return fail(KVS_ERR_HIP, "store check launch: %s", kvs::hip_error_string(e));
+    return KVS_OK;
+}
+
 static int attention_common(const kvs_store* store, int layer, const void* q, const int32_t* lens,
                             int lens_per_head, int lens_bias, int B, int T_new, float* out, void* workspace,
                             size_t workspace_bytes, void* stream, const void* k_new = nullptr,
@@ -478,7 +500,9 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     const Split s = choose_split(d, B, T_new, lens_per_head != 0);
     if (B > 65535 || (long)s.n_splits * s.n_col_groups > 65535)
         return fail(KVS_ERR_CAPACITY, "launch too large: B and splits x column groups are limited to 65535");
-    const size_t need = counter_bytes(d, B, s) + partial_floats(d, B, T_new, s) * sizeof(float);
+    if (counters_used(d, B, s) > kvs::kMaxCounters)        // only a forced split of a very large batch gets here
+        return fail(KVS_ERR_CAPACITY, "a split context is limited to %zu (sequence, kv head, column group) items", kvs::kMaxCounters);
+    const size_t need = kvs::kCounterRegionBytes + partial_floats(d, B, T_new, s) * sizeof(float);
     if (!workspace || workspace_bytes < need)
         return fail(KVS_ERR_INVALID_ARG, "workspace too small: need %zu bytes, got %zu", need, workspace_bytes);
     kvs::AttnArgs a;
@@ -493,7 +517,7 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     a.T_new = T_new;
     a.out = out;
     a.counters = static_cast<int32_t*>(workspace);
-    a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(d, B, s));
+    a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kvs::kCounterRegionBytes);
     a.pages_per_split = s.pages_per_split;
     a.n_splits = s.n_splits;
     a.wide_cols = s.wide_cols;

@@ -6,6 +6,14 @@
 
 namespace kvs {
 
+// Every workspace starts with a region of arrival counters of this fixed size (they must start,
+// and every call leaves them, at zero); the partial results of a call follow it.  The size does
+// not depend on the call's shape, so calls of different batch sizes, row counts and kinds can
+// take turns on one workspace without one call's partial results landing where another call
+// keeps its counters.  A call that splits work uses at most kMaxCounters of them.
+constexpr size_t kCounterRegionBytes = 64 * 1024;
+constexpr size_t kMaxCounters = kCounterRegionBytes / sizeof(int32_t);
+
 struct StoreView {
     void* pool;
     const int32_t* share_map;      // device [L]
@@ -51,6 +59,16 @@ struct CompactArgs {
     int32_t max_keep, B;
 };
 
+constexpr int kMaxCheckedLayers = 256;   // the host copies of the maps travel as kernel arguments
+
+struct CheckArgs {
+    StoreView st;
+    int32_t B;                                       // rows of the block table to look at
+    int32_t* report;                                 // device [2]
+    int32_t host_share_map[kMaxCheckedLayers];
+    int32_t host_slot_of_layer[kMaxCheckedLayers];
+};
+
 struct ProjectArgs {
     StoreView st;
     const void* x;          // device [B][T][hidden], bf16
@@ -69,6 +87,7 @@ struct ProjectArgs {
 int launch_append(const CopyArgs& a, void* stream);
 int launch_gather(const CopyArgs& a, void* stream);
 int launch_compact(const CompactArgs& a, void* stream);
+int launch_check_store(const CheckArgs& a, void* stream);
 int launch_attention(const AttnArgs& a, void* stream);
 int launch_project_append(ProjectArgs a, void* workspace, void* stream);
 size_t project_workspace_bytes(int Hkv, int head_dim, int hidden, int rows);

@@ -695,13 +695,16 @@ ProjectPlan plan_project(int Hkv, int head_dim, int hidden, int rows)
     return p;
 }
 
-size_t counter_bytes(size_t tiles) { return (tiles * sizeof(int32_t) + 255) / 256 * 256; }
 }  // namespace
+
+// The contraction is split only while the output tiles are fewer than kTargetWorkgroups, so the
+// counters in use (one per tile) always fit the fixed counter region at the workspace's start.
+static_assert(kTargetWorkgroups <= (long)kMaxCounters, "one arrival counter per output tile of a split contraction");
 
 size_t project_workspace_bytes(int Hkv, int head_dim, int hidden, int rows)
 {
     const ProjectPlan p = plan_project(Hkv, head_dim, hidden, rows);
-    return counter_bytes(p.tiles) + (p.k_splits > 1 ? (size_t)p.k_splits * p.tiles * p.partial_bytes : 0);
+    return kCounterRegionBytes + (p.k_splits > 1 ? (size_t)p.k_splits * p.tiles * p.partial_bytes : 0);
 }
 
 int launch_project_append(ProjectArgs a, void* workspace, void* stream)
@@ -710,7 +713,7 @@ int launch_project_append(ProjectArgs a, void* workspace, void* stream)
     const ProjectPlan p = plan_project(a.st.Hkv, a.st.head_dim, a.hidden, rows);
     a.k_splits = p.k_splits;
     a.counters = static_cast<int32_t*>(workspace);
-    a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(p.tiles));
+    a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterRegionBytes);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (p.pair) {
         const dim3 grid(8, (unsigned)((p.tiles + 7) / 8), 1);

@@ -249,7 +249,42 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
     }
 }
 
+// Debug aid: the kernels resolve slots and pages from the device copies of the maps and clamp
+// whatever they find into the pool, so a device map that differs from the host copies the checks
+// and the no-op decisions use, or a page-table entry outside the pool, stays silent.  One workgroup
+// counts both kinds of entries and writes the two counts.
+__global__ __launch_bounds__(1024) void check_store_kernel(CheckArgs a)
+{
+    const StoreView& st = a.st;
+    int bad_map = 0, bad_block = 0;
+    for (int l = threadIdx.x; l < st.L; l += blockDim.x)
+        bad_map += (st.share_map[l] != a.host_share_map[l]) + (st.slot_of_layer[l] != a.host_slot_of_layer[l]);
+    if (st.block_table) {
+        const size_t n = (size_t)a.B * st.max_blocks_per_seq;
+        for (size_t i = threadIdx.x; i < n; i += blockDim.x) {
+            const int blk = st.block_table[i];
+            bad_block += blk < 0 || blk >= st.num_blocks;
+        }
+    }
+    __shared__ int s_map, s_block;
+    if (threadIdx.x == 0) s_map = s_block = 0;
+    __syncthreads();
+    if (bad_map) atomicAdd(&s_map, bad_map);
+    if (bad_block) atomicAdd(&s_block, bad_block);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a.report[0] = s_map;
+        a.report[1] = s_block;
+    }
+}
+
 }  // namespace
+
+int launch_check_store(const CheckArgs& a, void* stream)
+{
+    hipLaunchKernelGGL(check_store_kernel, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(stream), a);
+    return (int)hipGetLastError();
+}
 
 int launch_append(const CopyArgs& a, void* stream)
 {

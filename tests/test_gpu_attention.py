@@ -21,7 +21,7 @@ def kb():
     from paper_2410_18517_amd import binding
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     yield binding
-    binding.kvs_set_split_tokens(0)
+    binding.kvs_testing_force_split_tokens(0)
 
 
 def _check_decode(kb, case, layers, seq_lens, tol):
@@ -71,7 +71,7 @@ def test_bf16_decode_shapes(kb, Hq, Hkv, d):
 
 @pytest.mark.parametrize("split_tokens", [0, 64, 128, 512])
 def test_bf16_edge_lengths_and_splits(kb, split_tokens):
-    kb.kvs_set_split_tokens(split_tokens)
+    kb.kvs_testing_force_split_tokens(split_tokens)
     try:
         share = np.array([0, 1, 1], np.int32)
         lens = [0, 1, 15, 16, 17, 63, 64, 65, 300, 333]
@@ -83,7 +83,7 @@ def test_bf16_edge_lengths_and_splits(kb, split_tokens):
         b = kb.kvs_decode_attention(case.store, 0, q.cuda(), np.full(len(lens), 336, np.int32))
         assert torch.equal(a, b)
     finally:
-        kb.kvs_set_split_tokens(0)
+        kb.kvs_testing_force_split_tokens(0)
 
 
 def test_many_splits_merge_is_exact_and_repeatable(kb):
@@ -93,7 +93,7 @@ def test_many_splits_merge_is_exact_and_repeatable(kb):
     case = Case(kb, 2, 8, 2, 128, 6, "bf16", 8192, share, seed=17)
     lens = np.array([8192, 8000, 4097, 64, 1, 0], np.int32)
     try:
-        kb.kvs_set_split_tokens(64)
+        kb.kvs_testing_force_split_tokens(64)
         q = case.q(1)
         want = orc.decode_attention(1, share, case.K, case.V, inputs.to_oracle_array(q), lens)
         first = None
@@ -102,11 +102,11 @@ def test_many_splits_merge_is_exact_and_repeatable(kb):
             first = got.clone() if first is None else first
             assert torch.equal(got, first)
         assert rel_l2_rows(first.cpu().numpy(), want).max() <= REL_L2_ATTENTION
-        kb.kvs_set_split_tokens(8192)                                    # one split: no merge at all
+        kb.kvs_testing_force_split_tokens(8192)                                    # one split: no merge at all
         single = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens).cpu().numpy()
         assert rel_l2_rows(single, want).max() <= REL_L2_ATTENTION
     finally:
-        kb.kvs_set_split_tokens(0)
+        kb.kvs_testing_force_split_tokens(0)
 
 
 # A decode launch sizes its context splits by the lengths it finds on the device: a batch far below
@@ -200,12 +200,12 @@ def test_bf16_flat_and_peaked_softmax(kb, gain):
     lens = np.array([1500, 700, 33], np.int32)
     q = (case.q(1).float() * gain).to(torch.bfloat16)
     for split in (0, 256):
-        kb.kvs_set_split_tokens(split)
+        kb.kvs_testing_force_split_tokens(split)
         got = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens).cpu().numpy()
         want = orc.decode_attention(1, share, case.K, case.V, inputs.to_oracle_array(q), lens)
         assert np.isfinite(got).all()
         assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION, (gain, split)
-    kb.kvs_set_split_tokens(0)
+    kb.kvs_testing_force_split_tokens(0)
     # rising scores: key j is a growing multiple of q's direction for head 0 of sequence 0
     k_up = torch.from_numpy(case.K[0].view(np.int16)).view(torch.bfloat16).clone()
     ramp = torch.linspace(-1.0, 1.0, 1500).view(1, 1500, 1, 1)
@@ -267,12 +267,17 @@ def test_causal_prefill(kb, dtype, Hq, Hkv, d, T_new):
             want = orc.shared_attention(layer, share, case.K, case.V, inputs.to_oracle_array(q), start)
             assert np.isfinite(got).all()
             assert rel_l2_rows(got, want).max() <= tol, (layer, start)
-    # the last prefill row is what the following decode step computes
+    # The last prefill row is what the following decode step computes (the oracle's pins include that
+    # identity): both calls are held to the oracle's decode result, each at the oracle tolerance.
+    # (The two GPU results are not compared with each other: two values within tol of a third are
+    # only within 2 tol of each other, and nothing in the method asks for more.)
     q = case.q(0, rows=T_new)
-    pre = kb.kvs_prefill_attention(case.store, 0, q.cuda(), np.array([10, 20, 30], np.int32))
-    dec = kb.kvs_decode_attention(case.store, 0, q[:, -1].contiguous().cuda(),
-                                  np.array([10, 20, 30], np.int32) + T_new)
-    assert rel_l2_rows(dec.cpu().numpy(), pre[:, -1].cpu().numpy().astype(np.float64)).max() <= REL_L2_ATTENTION
+    begin = np.array([10, 20, 30], np.int32)
+    pre = kb.kvs_prefill_attention(case.store, 0, q.cuda(), begin).cpu().numpy()
+    dec = kb.kvs_decode_attention(case.store, 0, q[:, -1].contiguous().cuda(), begin + T_new).cpu().numpy()
+    want = orc.decode_attention(0, share, case.K, case.V, inputs.to_oracle_array(q[:, -1].contiguous()), begin + T_new)
+    assert rel_l2_rows(dec, want).max() <= tol
+    assert rel_l2_rows(pre[:, -1], want).max() <= tol
 
 
 # Shapes that reach each instantiation of the shared-page prefill kernel (a workgroup's wavefronts
@@ -324,7 +329,7 @@ def test_shared_page_prefill_with_context_splits(kb, dtype, Hq, Hkv, B, T_new, c
     start = np.array([0, cap // 3 + 5, cap - T_new][:B], np.int32)
     start[-1] = cap - T_new
     q = case.q(1, rows=T_new)
-    assert kb.lib().kvs_set_split_tokens(split_tokens) == kb.KVS_OK
+    assert kb.lib().kvs_testing_force_split_tokens(split_tokens) == kb.KVS_OK
     try:
         for _ in range(2):                                         # twice: the counters must be left at zero
             got = kb.kvs_prefill_attention(case.store, 1, q.cuda(), start).cpu().numpy()
@@ -332,7 +337,7 @@ def test_shared_page_prefill_with_context_splits(kb, dtype, Hq, Hkv, B, T_new, c
             assert np.isfinite(got).all()
             assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
     finally:
-        assert kb.lib().kvs_set_split_tokens(0) == kb.KVS_OK
+        assert kb.lib().kvs_testing_force_split_tokens(0) == kb.KVS_OK
 
 
 # A workspace sized for up to 33 rows must serve a call of 32: with 64 (sequence, kv head) pairs, 33
@@ -446,7 +451,7 @@ def test_randomised_shapes_maps_and_lengths(kb):
                         seed=900 + case_id)
             lens = rng.integers(0, cap + 1, size=B).astype(np.int32)
             lens[rng.integers(0, B)] = cap
-            kb.kvs_set_split_tokens(int(rng.choice([0, 64, 256, 1024])))
+            kb.kvs_testing_force_split_tokens(int(rng.choice([0, 64, 256, 1024])))
             tol = 1e-5 if dtype == "f32" else REL_L2_ATTENTION
             for layer in rng.choice(L, size=min(L, 3), replace=False):
                 q = case.q(int(layer))
@@ -462,4 +467,4 @@ def test_randomised_shapes_maps_and_lengths(kb):
             want = orc.shared_attention(layer, share, case.K, case.V, inputs.to_oracle_array(q), start)
             assert rel_l2_rows(got, want).max() <= tol, (case_id, "prefill", T_new)
     finally:
-        kb.kvs_set_split_tokens(0)
+        kb.kvs_testing_force_split_tokens(0)

@@ -30,7 +30,7 @@ def test_decode_step_is_append_then_attention(kb, dtype, Hq, Hkv, d, split):
     K = [None if x is None else np.concatenate([x, np.zeros((B, cap - T0, Hkv, d), x.dtype)], 1) for x in case.K]
     V = [None if x is None else np.concatenate([x, np.zeros((B, cap - T0, Hkv, d), x.dtype)], 1) for x in case.V]
     tol = 1e-5 if dtype == "f32" else REL_L2_ATTENTION
-    assert kb.lib().kvs_set_split_tokens(split) == kb.KVS_OK
+    assert kb.lib().kvs_testing_force_split_tokens(split) == kb.KVS_OK
     try:
         for layer in (1, 2, 0):                                # donor, its recipient, an unrelated layer
             k_new = inputs.normal((B, 1, Hkv, d), 81, layer, 700, dtype=row_dt)
@@ -56,7 +56,7 @@ def test_decode_step_is_append_then_attention(kb, dtype, Hq, Hkv, d, split):
                 assert np.array_equal(inputs.to_oracle_array(kk)[b, 0], K[donor][b, lens[b] - 1])
                 assert np.array_equal(inputs.to_oracle_array(vv)[b, 0], V[donor][b, lens[b] - 1])
     finally:
-        assert kb.lib().kvs_set_split_tokens(0) == kb.KVS_OK
+        assert kb.lib().kvs_testing_force_split_tokens(0) == kb.KVS_OK
 
 
 def test_decode_step_edge_lengths(kb):

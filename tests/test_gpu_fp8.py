@@ -61,7 +61,7 @@ def test_decode_over_fp8_slots(kb, Hq, Hkv, d, split):
     case = Case(kb, L, Hq, Hkv, d, B, "fp8", cap, share, paged=True, seed=71)
     assert case.store.pool.numel() == 2 * (B * 33 + 3) * Hkv * 2 * 16 * d      # one byte per element
     lens = np.array([cap, 301, 16], np.int32)
-    assert kb.lib().kvs_set_split_tokens(split) == kb.KVS_OK
+    assert kb.lib().kvs_testing_force_split_tokens(split) == kb.KVS_OK
     try:
         for layer in range(L):
             q = case.q(layer)
@@ -69,7 +69,7 @@ def test_decode_over_fp8_slots(kb, Hq, Hkv, d, split):
             want = orc.decode_attention(layer, share, case.K, case.V, inputs.to_oracle_array(q), lens)
             assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION, layer
     finally:
-        assert kb.lib().kvs_set_split_tokens(0) == kb.KVS_OK
+        assert kb.lib().kvs_testing_force_split_tokens(0) == kb.KVS_OK
 
 
 def test_decode_step_and_prefill_over_fp8_slots(kb):

@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 def kb():
     from paper_2410_18517_amd import binding
     assert torch.cuda.is_available(), "GPU tests need a GPU"
-    binding.kvs_set_split_tokens(0)
+    binding.kvs_testing_force_split_tokens(0)
     return binding
 
 

@@ -37,7 +37,7 @@ def test_decode_steps_replayed_from_a_graph(kb, split, cap, T0):
     k_buf = torch.zeros((L, B, 1, Hkv, d), dtype=torch.bfloat16, device="cuda")
     v_buf = torch.zeros_like(k_buf)
     out_buf = torch.zeros((L, B, Hq, d), dtype=torch.float32, device="cuda")
-    assert kb.lib().kvs_set_split_tokens(split) == kb.KVS_OK
+    assert kb.lib().kvs_testing_force_split_tokens(split) == kb.KVS_OK
     try:
         ws = case.store.workspace(B, 1)                         # sized for this split setting, before the recording
         graph = torch.cuda.CUDAGraph()
@@ -65,4 +65,4 @@ def test_decode_steps_replayed_from_a_graph(kb, split, cap, T0):
                 eager = kb.kvs_decode_attention(case.store, layer, q_buf[layer], lens_dev, workspace=ws).cpu().numpy()
                 assert rel_l2_rows(eager, want).max() <= REL_L2_ATTENTION, (step, layer)
     finally:
-        assert kb.lib().kvs_set_split_tokens(0) == kb.KVS_OK
+        assert kb.lib().kvs_testing_force_split_tokens(0) == kb.KVS_OK

@@ -94,7 +94,7 @@ def test_attention_over_kept_sets_matches_the_oracle(kb, dtype, d, Hq, Hkv, spli
         assert kb.kvs_compact_kv(case.store, donor, idx, cnt) == kb.KVS_OK
         kv_lens[donor] = cnt
     q = inputs.normal((B, Hq, d), 32, 900, dtype=case.row_dtype)
-    assert kb.lib().kvs_set_split_tokens(split) == kb.KVS_OK
+    assert kb.lib().kvs_testing_force_split_tokens(split) == kb.KVS_OK
     try:
         for layer in range(L):
             got = kb.kvs_decode_attention_per_head(case.store, layer, q.cuda(), kv_lens).cpu().numpy()
@@ -105,7 +105,7 @@ def test_attention_over_kept_sets_matches_the_oracle(kb, dtype, d, Hq, Hkv, spli
                 group = Hq // Hkv
                 assert np.all(got[2, :group] == 0)            # the empty head's query heads
     finally:
-        assert kb.lib().kvs_set_split_tokens(0) == kb.KVS_OK
+        assert kb.lib().kvs_testing_force_split_tokens(0) == kb.KVS_OK
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp8"])

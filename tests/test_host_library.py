@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "kvs.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("kvs.h", "kvs_testing.h"))
     body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", body))
     declared -= {"kvs_accept_fn"}
@@ -41,7 +41,7 @@ def test_share_map_matches_oracle_bitwise(L, C_, order):
 
 
 def test_random_sharing_baseline_is_the_walk_over_a_random_ranking():
-    """Sec. 5.2 compares against randomly chosen pairs at 25 % compression, three draws: a matrix of
+    """Sec. 5.3 compares against randomly chosen pairs at 25 % compression, three draws: a matrix of
     random values and no similarity test gives such a strategy, valid and different per draw."""
     L, C_ = 40, 10
     maps = []
@@ -109,14 +109,14 @@ def test_store_and_workspace_sizes():
     assert lib.kvs_workspace_bytes(C.byref(d), 0, 1) == 0
     assert lib.kvs_distance_workspace_bytes(129) == 0 and lib.kvs_distance_workspace_bytes(48) > 0
     assert lib.kvs_distance_workspace_bytes(128) > lib.kvs_distance_workspace_bytes(64)      # per pair block of layers
-    # projection: 2*Hkv*(d/32) output tiles per 16 rows, one counter each (padded to 256 bytes), and
-    # when the contraction is split, one 256-thread pair of floats per tile and split
+    # projection: the fixed 64 KiB counter region, then, when the contraction is split, one 256-thread
+    # pair of floats per output tile (2*Hkv*(d/32) per 16 rows) and split
     big = _desc(Hq=32, Hkv=8)
-    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 4, 1) == 256 + 4 * 64 * 256 * 8
-    assert lib.kvs_project_workspace_bytes(C.byref(big), 128, 4, 1) == 256          # nothing to split
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 4, 1) == 65536 + 4 * 64 * 256 * 8
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 128, 4, 1) == 65536        # nothing to split
     # more than 32 rows: 256-row tiles of a whole head, 512 threads x 64 accumulators per tile and split
-    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 64, 64) == 2 * 8 * 16 * 4      # enough tiles already
-    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 16, 64) == 256 + 4 * 64 * 512 * 64 * 4
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 64, 64) == 65536                  # enough tiles already
+    assert lib.kvs_project_workspace_bytes(C.byref(big), 4096, 16, 64) == 65536 + 4 * 64 * 512 * 64 * 4
     assert lib.kvs_project_workspace_bytes(C.byref(big), 100, 4, 1) == 0
     assert lib.kvs_project_workspace_bytes(C.byref(_desc(dtype=kb.KVS_F32)), 4096, 4, 1) == 0
 
@@ -175,13 +175,13 @@ def test_entry_points_reject_bad_arguments_without_touching_the_gpu():
         == kb.KVS_ERR_UNSUPPORTED
     # split workspace too small (4 blocks per sequence, forced 64-token splits => 1 split... use more blocks)
     big = _fake_store(max_blocks_per_seq=64, num_blocks=64)
-    assert lib.kvs_set_split_tokens(64) == kb.KVS_OK
+    assert lib.kvs_testing_force_split_tokens(64) == kb.KVS_OK
     try:
         assert lib.kvs_decode_attention(C.byref(big), 0, p, p, 1, p, p, 16, None) == kb.KVS_ERR_INVALID_ARG
         assert "workspace" in kb.last_error()
     finally:
-        assert lib.kvs_set_split_tokens(0) == kb.KVS_OK
-    assert lib.kvs_set_split_tokens(100) == kb.KVS_ERR_INVALID_ARG
+        assert lib.kvs_testing_force_split_tokens(0) == kb.KVS_OK
+    assert lib.kvs_testing_force_split_tokens(100) == kb.KVS_ERR_INVALID_ARG
     # fused projection: recipient layers are a host-side no-op; bad shapes and a missing workspace are errors
     proj = lambda layer, hidden=256, cos=None, sin=None, npos=0, B=1, T=1, ws=p, nws=1 << 30, x=p: \
         lib.kvs_project_append_kv(C.byref(st), layer, x, hidden, p, p, cos, sin, npos, p, B, T, ws, nws, None)
@@ -208,6 +208,10 @@ def test_entry_points_reject_bad_arguments_without_touching_the_gpu():
     assert lib.kvs_decode_attention_per_head(C.byref(st), 0, p, None, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_decode_attention_per_head(C.byref(st), 0, None, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_decode_attention_per_head(C.byref(st), 5, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
+    # the store check
+    assert lib.kvs_check_store(C.byref(st), 1, None, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_check_store(C.byref(st), -1, p, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_check_store(None, 1, p, None) == kb.KVS_ERR_INVALID_ARG
     # the one-launch decode step
     assert lib.kvs_decode_step(C.byref(st), 0, p, None, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_decode_step(C.byref(st), 0, None, p, p, p, 1, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
@@ -219,3 +223,4 @@ def test_entry_points_reject_bad_arguments_without_touching_the_gpu():
     assert lib.kvs_layer_distance(p, 1, 2, 12, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_UNSUPPORTED
     assert lib.kvs_layer_distance(p, 0, 2, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_layer_distance(p, 1, 2, 8, 0, p, p, p, p, 16, None) == kb.KVS_ERR_INVALID_ARG
+

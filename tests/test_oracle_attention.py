@@ -214,3 +214,40 @@ def test_append_writes_only_own_cache_layers():
     assert orc.append_kv(2, share, Ks, Vs, k, v, start) is False
     np.testing.assert_array_equal(Ks[0][1, 5:7], k[1]); np.testing.assert_array_equal(Vs[0][0, 0:2], v[0])
     assert Ks[0][1, :5].max() == 0 and Ks[1].max() == 0
+
+
+def test_paged_append_lands_where_the_paged_reader_looks():
+    """The append's page addressing (block = table[b][j / block size], row j % block size) is pinned
+    against an independent statement of it: rows appended through a permuted table, in several
+    calls of ragged sizes that straddle page ends, then attended to through the same table, give
+    bitwise the result of the same appends to a plain contiguous cache; blocks no sequence owns
+    keep their NaN fill, so a row written to a wrong block would either be missed or poison a result."""
+    B, Hq, Hkv, d, bs, nblk = 2, 4, 2, 8, 4, 5
+    T = bs * nblk
+    share = np.array([0, 0], np.int32)
+    table = RNG.permutation(B * nblk + 3)[:B * nblk].reshape(B, nblk).astype(np.int32)
+    Kc, Vc = [np.zeros((B, T, Hkv, d), np.float32), None], [np.zeros((B, T, Hkv, d), np.float32), None]
+    Kp = [np.full((B * nblk + 3, bs, Hkv, d), np.nan, np.float32), None]
+    Vp = [np.full((B * nblk + 3, bs, Hkv, d), np.nan, np.float32), None]
+    pos = np.array([0, 0])
+    for rows in (3, 6, 1, 7):                                 # 17 of the 20 positions, page ends crossed mid-call
+        k, v = _f32(B, rows, Hkv, d), _f32(B, rows, Hkv, d)
+        assert orc.append_kv(0, share, Kc, Vc, k, v, pos) is True
+        assert orc.append_kv(0, share, Kp, Vp, k, v, pos, block_table=table) is True
+        assert orc.append_kv(1, share, Kp, Vp, k, v, pos, block_table=table) is False    # the recipient stores nothing
+        pos = pos + rows
+    owned = np.zeros(B * nblk + 3, bool)
+    owned[table.ravel()] = True
+    assert np.isnan(Kp[0][~owned]).all() and np.isnan(Vp[0][~owned]).all()
+    q = _f32(B, Hq, d)
+    for n in ([17, 17], [16, 5], [1, 13]):
+        for layer in (0, 1):
+            want = orc.decode_attention(layer, share, Kc, Vc, q, np.asarray(n))
+            got = orc.decode_attention(layer, share, Kp, Vp, q, np.asarray(n), block_table=table)
+            assert np.isfinite(got).all()
+            np.testing.assert_array_equal(got, want)
+    # and position by position against the definition of the page table
+    for b in range(B):
+        for j in range(17):
+            np.testing.assert_array_equal(Kp[0][table[b, j // bs], j % bs], Kc[0][b, j])
+            np.testing.assert_array_equal(Vp[0][table[b, j // bs], j % bs], Vc[0][b, j])
