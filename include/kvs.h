@@ -212,6 +212,22 @@ int kvs_decode_attention(const kvs_store* store, int layer, const void* q,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * kvs_decode_attention for callers that cannot allocate device memory or carry a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * without the workspace, same kernels, same result bit for bit; the scratch is an 8 MiB device
+ * array inside the library (kvs_noalloc_scratch_bytes()), one copy per GPU, held until the process
+ * ends.  The call allocates and frees nothing.  Shapes whose kvs_workspace_bytes(desc, B, 1)
+ * exceeds the array are refused with KVS_ERR_CAPACITY before any launch.  All such calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads)
+ * race on it; calls in stream order do not.  The first call on a device looks up the array's
+ * address there (hipGetSymbolAddress, no allocation) and should be made outside a graph capture.
+ */
+int kvs_decode_attention_noalloc(const kvs_store* store, int layer, const void* q,
+                                 const int32_t* seq_lens, int B, float* out, void* stream);
+
+size_t kvs_noalloc_scratch_bytes(void);
+
+/*
  * One decode step in one launch: kvs_append_kv(k_new, v_new at position seq_lens[b] - 1) followed
  * by kvs_decode_attention(q, seq_lens), for the layers that keep their own cache; for a layer
  * that reads a donor's cache k_new and v_new are ignored and the call is kvs_decode_attention

@@ -26,7 +26,7 @@ EXPORTS = [
     "kvs_layer_distance", "kvs_distance_workspace_bytes", "kvs_avg_cos_sim", "kvs_cos_sim_workspace_bytes",
     "kvs_project_append_kv", "kvs_project_workspace_bytes",
     "kvs_compact_kv", "kvs_append_kv_per_head", "kvs_decode_attention_per_head", "kvs_decode_step",
-    "kvs_check_store",
+    "kvs_check_store", "kvs_decode_attention_noalloc", "kvs_noalloc_scratch_bytes",
 ]
 
 
@@ -80,6 +80,10 @@ def lib():
         L.kvs_decode_attention.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvs_decode_attention_per_head.argtypes = L.kvs_decode_attention.argtypes
+        L.kvs_decode_attention_noalloc.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                                   C.c_void_p, C.c_void_p]
+        L.kvs_noalloc_scratch_bytes.restype = C.c_size_t
+        L.kvs_noalloc_scratch_bytes.argtypes = []
         L.kvs_decode_step.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.kvs_prefill_attention.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
@@ -307,6 +311,19 @@ def kvs_decode_attention(store: KVStore, layer, q, seq_lens, out=None, workspace
     ws = workspace if workspace is not None else store.workspace(B, 1)
     _check(lib().kvs_decode_attention(C.byref(store.c), int(layer), q.data_ptr(), sl.data_ptr(), B,
                                       out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def kvs_decode_attention_noalloc(store: KVStore, layer, q, seq_lens, out):
+    """kvs_decode_attention on the library's built-in scratch: no workspace; `out` is the caller's, fp32 [B, Hq, d]."""
+    assert q.is_cuda and q.is_contiguous() and q.dtype == store.torch_dtype
+    B = q.shape[0]
+    assert tuple(q.shape) == (B, store.desc.Hq, store.desc.head_dim)
+    assert out.is_cuda and out.is_contiguous() and out.dtype == torch.float32 and tuple(out.shape) == tuple(q.shape)
+    sl = _dev_i32(seq_lens, store.device)
+    assert sl.numel() == B
+    _check(lib().kvs_decode_attention_noalloc(C.byref(store.c), int(layer), q.data_ptr(), sl.data_ptr(), B,
+                                              out.data_ptr(), _stream()))
     return out
 
 

@@ -5,7 +5,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvs.so")
-SOURCES = ["kvs_host.cpp", "kvs_store_ops.hip", "kvs_attention.hip", "kvs_distance.hip", "kvs_similarity.hip", "kvs_projection.hip"]
+SOURCES = ["kvs_host.cpp", "kvs_store_ops.hip", "kvs_attention.hip", "kvs_distance.hip", "kvs_similarity.hip", "kvs_projection.hip",
+           "kvs_static.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

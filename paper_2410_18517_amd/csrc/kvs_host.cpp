@@ -223,6 +223,10 @@ size_t partial_floats(const kvs_desc* d, int B, int T_new, const Split& s)
 
 }  // namespace
 
+namespace kvs {
+int report_error(int code, const char* message) { return fail(code, "%s", message); }
+}  // namespace kvs
+
 extern "C" {
 
 const char* kvs_last_error(void) { return g_last_error.c_str(); }

@@ -98,5 +98,6 @@ int launch_cos_sim(const void* a, const void* b, int S, size_t N, int dtype, int
                    void* stream);
 size_t cos_sim_workspace_bytes(int S);
 const char* hip_error_string(int err);
+int report_error(int code, const char* message);   // sets what kvs_last_error() returns on this thread; returns code
 
 }  // namespace kvs

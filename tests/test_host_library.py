@@ -224,3 +224,23 @@ def test_entry_points_reject_bad_arguments_without_touching_the_gpu():
     assert lib.kvs_layer_distance(p, 0, 2, 8, 0, p, p, p, p, 1 << 30, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_layer_distance(p, 1, 2, 8, 0, p, p, p, p, 16, None) == kb.KVS_ERR_INVALID_ARG
 
+
+def test_noalloc_entry_point_refuses_shapes_beyond_its_scratch():
+    """Decided on the host, before the device is asked for anything: the built-in scratch has a fixed
+    size, and a shape whose workspace need exceeds it is refused with the reason."""
+    lib = kb.lib()
+    assert lib.kvs_noalloc_scratch_bytes() == 8 << 20
+    wide = kb.kvs_desc(2, 2, 16, 1, 128, kb.KVS_BF16, 16, 1 << 16, 1 << 16)
+    assert 0 < lib.kvs_workspace_bytes(C.byref(wide), 64, 1) <= lib.kvs_noalloc_scratch_bytes()
+    big = kb.kvs_store(wide, 1, 1, 1, None, 1, 1)                 # never dereferenced: the size check comes first
+    assert lib.kvs_testing_force_split_tokens(64) == kb.KVS_OK    # 64-token splits of a 2^20-token context: far more partial states
+    try:
+        assert lib.kvs_workspace_bytes(C.byref(wide), 64, 1) > lib.kvs_noalloc_scratch_bytes()
+        assert lib.kvs_decode_attention_noalloc(C.byref(big), 0, 1, 1, 64, 1, None) == kb.KVS_ERR_CAPACITY
+        assert "scratch" in kb.last_error()
+    finally:
+        assert lib.kvs_testing_force_split_tokens(0) == kb.KVS_OK
+    assert lib.kvs_decode_attention_noalloc(None, 0, 1, 1, 64, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_attention_noalloc(C.byref(big), 0, 1, 1, 0, 1, None) == kb.KVS_ERR_INVALID_ARG
+    assert lib.kvs_decode_attention_noalloc(C.byref(kb.kvs_store(kb.kvs_desc(2, 2, 16, 1, 96, kb.KVS_BF16, 16, 64, 64), 1, 1, 1, None, 1, 1)),
+                                            0, 1, 1, 1, 1, None) == kb.KVS_ERR_INVALID_ARG
