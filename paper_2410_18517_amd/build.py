@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvs.so")
-SOURCES = ["kvs_host.cpp", "kvs_store_ops.hip", "kvs_attention.hip", "kvs_distance.hip", "kvs_similarity.hip", "kvs_projection.hip",
+SOURCES = ["kvs_host.cpp", "kvs_store_ops.hip", "kvs_attention.hip", "kvs_decode.hip", "kvs_distance.hip", "kvs_similarity.hip", "kvs_projection.hip",
            "kvs_static.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
@@ -20,7 +20,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "kvs_internal.h"), os.path.join(CSRC, "kvs_device.h"),
+    deps = sources() + [os.path.join(CSRC, "kvs_internal.h"), os.path.join(CSRC, "kvs_device.h"), os.path.join(CSRC, "kvs_attn_tiles.h"), os.path.join(CSRC, "kvs_flat_plan.h"),
                         os.path.join(HERE, "..", "include", "kvs.h"), os.path.join(HERE, "..", "include", "kvs_testing.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 

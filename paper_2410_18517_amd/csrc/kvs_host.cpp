@@ -2,6 +2,7 @@
 // Everything that can be decided without the GPU is decided here, before any HIP call.
 #include "../../include/kvs.h"
 #include "../../include/kvs_testing.h"
+#include "kvs_flat_plan.h"
 #include "kvs_internal.h"
 
 #include <algorithm>
@@ -179,21 +180,22 @@ Split choose_split(const kvs_desc* d, int B, int T_new, bool per_head_lens = fal
     pps = std::max(kMinPagesPerSplit, std::min(pps, (max_pages + 3) / 4 * 4));
     s.pages_per_split = pps;
     s.n_splits = (max_pages + pps - 1) / pps;
-    // (with more than two workgroups per compute unit the order in which they are handed out evens
-    // out unequal lengths by itself, and every workgroup would scan that many more lengths)
-    // (and the kernel adds up all lengths in pages as 32-bit integers)
+    // (the kernels add up all lengths in pages, or in groups of eight pages, as 32-bit integers)
+    if (T_new == 1 && forced == 0 && !per_head_lens && B <= 64 && (size_t)B * d->Hkv <= kvs::kMaxCounters &&
+        items * max_pages < (1L << 28)) {
+        // One length per sequence, at most 64 sequences: the launch's pages are shared out by tokens
+        // among a fixed number of workgroups, whatever the lengths turn out to be on the device (one
+        // workgroup per compute unit; at least one per kv head, which the rows of empty sequences need).
+        const long octets = (long)B * d->Hkv * ((max_pages + 7) / 8);
+        s.adaptive = 3;
+        s.n_items = (int)std::max<long>(std::min<long>(kTargetWorkgroups, octets), d->Hkv);
+        return s;
+    }
+    // Per-head lengths, or more than 64 sequences: the split kernel, which sizes its splits on the
+    // device while the (sequence, kv head) pairs are few.  (With more than two workgroups per compute
+    // unit the order in which they are handed out evens out unequal lengths by itself, and every
+    // workgroup would scan that many more lengths.)
     if (T_new == 1 && forced == 0 && items <= 2 * kTargetWorkgroups && items * max_pages < (1L << 30)) {
-        if (!per_head_lens && B <= 64 && want > 1) {
-            // One length per sequence, few sequences: the kernel also numbers its work items itself,
-            // every sequence as many as its length asks for.  With pages per split >= all pages /
-            // (B * want) the items number at most B * (want + 1), whatever the lengths.  (Not where
-            // every (sequence, kv head) already has a compute unit to itself, want == 1: cutting the
-            // longer sequences in two there only doubles workgroups up on some units.)
-            s.adaptive = 2;
-            s.want_splits = (int)want;
-            s.n_items = B * ((int)want + 1);
-            return s;
-        }
         const int spare = (int)std::min(most, kSplitHeadroom * want);
         if (spare > 1) {
             s.adaptive = 1;
@@ -216,7 +218,7 @@ size_t counters_used(const kvs_desc* d, int B, const Split& s)
 
 size_t partial_floats(const kvs_desc* d, int B, int T_new, const Split& s)
 {
-    if (s.adaptive == 2) return (size_t)s.n_items * d->Hq * (size_t)(d->head_dim + 2);   // a record per (item, query head)
+    if (s.adaptive == 3) return kvs::decode_flat_partial_floats(s.n_items, B, d->Hq, d->Hkv, d->head_dim);
     if (s.n_splits <= 1) return 0;
     return (size_t)B * T_new * d->Hq * s.n_splits * (size_t)(d->head_dim + 2);
 }
@@ -303,6 +305,21 @@ int kvs_testing_force_split_tokens(int tokens)
     if (tokens < 0 || tokens % 64 != 0) return fail(KVS_ERR_INVALID_ARG, "split tokens must be 0 or a multiple of 64");
     g_split_tokens.store(tokens);
     return KVS_OK;
+}
+
+int kvs_testing_flat_share(int i, int n, int total, int* first, int* count)
+{
+    if (n <= 0 || i < 0 || i >= n || total < 0 || !first || !count) return fail(KVS_ERR_INVALID_ARG, "need 0 <= i < n, total >= 0");
+    const kvs::FlatShare s = kvs::flat_share(i, n, total);
+    *first = s.lo;
+    *count = s.count;
+    return KVS_OK;
+}
+
+int kvs_testing_flat_owner(int o, int n, int total)
+{
+    if (n <= 0 || o < 0 || o >= total) return -1;
+    return kvs::flat_owner(o, n, total);
 }
 
 size_t kvs_workspace_bytes(const kvs_desc* d, int B, int max_q_rows)
@@ -528,7 +545,8 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     a.adaptive = s.adaptive;
     a.want_splits = s.want_splits;
     a.n_items = s.n_items;
-    if (int e = kvs::launch_attention(a, stream)) return fail(KVS_ERR_HIP, "attention launch: %s", kvs::hip_error_string(e));
+    if (int e = s.adaptive == 3 ? kvs::launch_decode_flat(a, stream) : kvs::launch_attention(a, stream))
+        return fail(KVS_ERR_HIP, "attention launch: %s", kvs::hip_error_string(e));
     return KVS_OK;
 }
 

@@ -35,10 +35,10 @@ struct AttnArgs {
     float* partials;        // device fp32 [B][T_new][Hq][n_splits][D + 2]
     int32_t* counters;      // device [B][Hkv][n_col_groups], zero between calls
     int32_t pages_per_split, n_splits;   // n_splits: split indices in the grid and records per row in partials
-    int32_t adaptive;       // decode: 1 = the kernel sizes the splits by the lengths it finds (pages_per_split is then what
-    int32_t want_splits;    //   full sequences get); want_splits: workgroups a sequence of mean length is shared among.
-    int32_t n_items;        //   2 = it also numbers its work items itself: grid (Hkv, n_items), partials one record per
-                            //   (item, query head), n_splits = the splits of a full sequence
+    int32_t adaptive;       // decode: 1 = the split kernel sizes the splits by the lengths it finds (pages_per_split is then
+    int32_t want_splits;    //   what full sequences get); want_splits: workgroups a sequence of mean length is shared among.
+    int32_t n_items;        //   3 = the kernel of kvs_decode.hip: n_items workgroups share the launch's pages out by
+                            //   tokens; partials one record per (workgroup + segment, head of the group)
     int32_t wide_cols;      // prefill: 0 = the page-splitting kernel, else columns per workgroup of the shared-page kernel (64, 128, 256)
 };
 
@@ -89,6 +89,8 @@ int launch_gather(const CopyArgs& a, void* stream);
 int launch_compact(const CompactArgs& a, void* stream);
 int launch_check_store(const CheckArgs& a, void* stream);
 int launch_attention(const AttnArgs& a, void* stream);
+int launch_decode_flat(const AttnArgs& a, void* stream);          // a.adaptive == 3: grid of a.n_items workgroups
+size_t decode_flat_partial_floats(int n_wg, int B, int Hq, int Hkv, int head_dim);
 int launch_project_append(ProjectArgs a, void* workspace, void* stream);
 size_t project_workspace_bytes(int Hkv, int head_dim, int hidden, int rows);
 int launch_layer_distance(const void* kv, int S, int L, size_t N, int dtype, float* dK2, float* dV2,

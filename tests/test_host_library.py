@@ -244,3 +244,26 @@ def test_noalloc_entry_point_refuses_shapes_beyond_its_scratch():
     assert lib.kvs_decode_attention_noalloc(C.byref(big), 0, 1, 1, 0, 1, None) == kb.KVS_ERR_INVALID_ARG
     assert lib.kvs_decode_attention_noalloc(C.byref(kb.kvs_store(kb.kvs_desc(2, 2, 16, 1, 96, kb.KVS_BF16, 16, 64, 64), 1, 1, 1, None, 1, 1)),
                                             0, 1, 1, 1, 1, None) == kb.KVS_ERR_INVALID_ARG
+
+
+def test_token_shares_of_a_decode_launch_partition_the_line():
+    """The plan the decode kernel derives on the device, against brute force: n shares tile the line
+    of octets without gap or overlap, differ by at most one octet, and the owner look-up inverts them."""
+    lib = kb.lib()
+    first, count = C.c_int(0), C.c_int(0)
+    for n in (1, 2, 7, 8, 256):
+        for total in list(range(0, 40)) + [255, 256, 257, 511, 2720, 8192, 10240, 65537]:
+            at, sizes, owner = 0, [], []
+            for i in range(n):
+                assert lib.kvs_testing_flat_share(i, n, total, C.byref(first), C.byref(count)) == kb.KVS_OK
+                assert first.value == at and count.value >= 0
+                at += count.value
+                sizes.append(count.value)
+                owner += [i] * count.value
+            assert at == total and max(sizes) - min(sizes) <= 1
+            assert sizes == sorted(sizes, reverse=True)                      # the larger shares come first
+            step = max(1, total // 300)
+            for o in list(range(0, total, step)) + [total - 1] * (total > 0):
+                assert lib.kvs_testing_flat_owner(o, n, total) == owner[o], (n, total, o)
+            assert lib.kvs_testing_flat_owner(total, n, total) == -1
+    assert lib.kvs_testing_flat_share(3, 3, 10, C.byref(first), C.byref(count)) == kb.KVS_ERR_INVALID_ARG
