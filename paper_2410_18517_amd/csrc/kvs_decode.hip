@@ -35,6 +35,21 @@ constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 static_assert(kOctetPages == 2 * kWaves, "an octet is one pair of pages per wavefront");
 
+// A page through a buffer descriptor of `bytes` bytes (the page's size, or 0 for a page that does
+// not exist: every load is then out of range, returns zeros and sends nothing to memory).  The load
+// instructions are issued either way, which keeps the number of loads per step fixed.  Streamed
+// past the caches like load_page.
+template <typename Regs>
+__device__ __forceinline__ void load_page_checked(Regs& r, const void* page, unsigned bytes, int lane)
+{
+    constexpr int n = sizeof(r.k) / sizeof(r.k[0]);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(page), 0, (int)bytes, 0x00020000);
+#pragma unroll
+    for (int s = 0; s < n; ++s) r.k[s] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16 + s * 1024, 0, 2);
+#pragma unroll
+    for (int s = 0; s < n; ++s) r.v[s] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16 + (n + s) * 1024, 0, 2);
+}
+
 // A place on the line of octets: kv head, sequence, octet inside the sequence (of `octs`).
 struct Cursor {
     int g, b, oi, octs;
@@ -134,7 +149,10 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
     };
     // The pair of pages this wavefront takes of the octet at c (live: the octet belongs to this
     // workgroup's share).  Page-table look-ups are scalar loads and may sit in branches; the page
-    // loads themselves are unconditional.
+    // loads themselves are unconditional: a page that does not exist is read through an empty
+    // buffer descriptor, whose loads return zeros without touching memory.
+    constexpr unsigned kPageBytes = 2u * kPageTokens * D * (kFp8 ? 1u : 2u);       // keys and values of one page
+    const size_t elem_bytes = kFp8 ? 1 : 2;
     auto fetch = [&](const Cursor& c, bool live, Raw& ra, Raw& rb, bool guessed, int j) {
         const int pa = c.oi * kOctetPages + 2 * wave;
         const int pages = live ? __builtin_amdgcn_readlane(pages_lane, c.b) : 0;
@@ -150,8 +168,8 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
             blk = blk < 0 ? 0 : (blk >= st.num_blocks ? st.num_blocks - 1 : blk);
             off_b = page_offset(st, slot, blk, c.g);
         }
-        load_page(ra, pool, off_a, lane);
-        load_page(rb, pool, off_b, lane);
+        load_page_checked(ra, static_cast<const char*>(pool) + off_a * elem_bytes, pa < pages ? kPageBytes : 0u, lane);
+        load_page_checked(rb, static_cast<const char*>(pool) + off_b * elem_bytes, pa + 1 < pages ? kPageBytes : 0u, lane);
     };
 
     const unsigned short* qbase = static_cast<const unsigned short*>(a.q);
