@@ -22,6 +22,14 @@ extern "C" {
 int kvs_testing_force_split_tokens(int tokens);
 
 /*
+ * Workgroups of a decode launch that shares its pages out by tokens (0: the built-in choice, one
+ * per compute unit; never fewer than the store has kv heads).  With a handful of workgroups every
+ * share holds many sequences, and one with thousands the shares are single octets, which a test
+ * cannot arrange otherwise.  Process-wide; query the workspace size again after changing it.
+ */
+int kvs_testing_set_decode_workgroups(int n);
+
+/*
  * The integer plan by which a decode launch shares out its pages by tokens, as the kernel computes
  * it on the device, for a host-side check against brute force: a line of `total` octets (eight
  * pages each) is cut into n shares that differ by at most one octet.  kvs_testing_flat_share

@@ -27,7 +27,7 @@ EXPORTS = [
     "kvs_project_append_kv", "kvs_project_workspace_bytes",
     "kvs_compact_kv", "kvs_append_kv_per_head", "kvs_decode_attention_per_head", "kvs_decode_step",
     "kvs_check_store", "kvs_decode_attention_noalloc", "kvs_noalloc_scratch_bytes",
-    "kvs_testing_flat_share", "kvs_testing_flat_owner",
+    "kvs_testing_flat_share", "kvs_testing_flat_owner", "kvs_testing_set_decode_workgroups",
 ]
 
 
@@ -92,6 +92,7 @@ def lib():
         L.kvs_testing_force_split_tokens.argtypes = [C.c_int]
         L.kvs_testing_flat_share.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.kvs_testing_flat_owner.argtypes = [C.c_int, C.c_int, C.c_int]
+        L.kvs_testing_set_decode_workgroups.argtypes = [C.c_int]
         L.kvs_check_store.argtypes = [C.POINTER(kvs_store), C.c_int, C.c_void_p, C.c_void_p]
         L.kvs_layer_distance.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_size_t, C.c_int, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]

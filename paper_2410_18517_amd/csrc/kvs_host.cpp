@@ -30,6 +30,7 @@ int fail(int code, const char* fmt, ...)
 }
 
 std::atomic<int> g_split_tokens{0};
+std::atomic<int> g_decode_workgroups{0};
 
 // Workgroups the decode grid should at least reach: one per compute unit.  Measured on
 // MI355X, four wavefronts per compute unit with three pages in flight each already saturate
@@ -188,7 +189,8 @@ Split choose_split(const kvs_desc* d, int B, int T_new, bool per_head_lens = fal
         // workgroup per compute unit; at least one per kv head, which the rows of empty sequences need).
         const long octets = (long)B * d->Hkv * ((max_pages + 7) / 8);
         s.adaptive = 3;
-        s.n_items = (int)std::max<long>(std::min<long>(kTargetWorkgroups, octets), d->Hkv);
+        const int forced_grid = g_decode_workgroups.load();
+        s.n_items = (int)std::max<long>(std::min<long>(forced_grid > 0 ? forced_grid : kTargetWorkgroups, octets), d->Hkv);
         return s;
     }
     // Per-head lengths, or more than 64 sequences: the split kernel, which sizes its splits on the
@@ -304,6 +306,13 @@ int kvs_testing_force_split_tokens(int tokens)
 {
     if (tokens < 0 || tokens % 64 != 0) return fail(KVS_ERR_INVALID_ARG, "split tokens must be 0 or a multiple of 64");
     g_split_tokens.store(tokens);
+    return KVS_OK;
+}
+
+int kvs_testing_set_decode_workgroups(int n)
+{
+    if (n < 0 || n > 65535) return fail(KVS_ERR_INVALID_ARG, "need 0 <= n <= 65535");
+    g_decode_workgroups.store(n);
     return KVS_OK;
 }
 

@@ -98,3 +98,21 @@ def test_step_with_its_own_token_across_shares(kb, dtype):
         if 1 <= lens[b] <= cap:
             kk, vv = kb.kvs_gather_kv(case.store, 0, int(lens[b]) - 1, 1, B)
             assert np.array_equal(inputs.to_oracle_array(kk)[b, 0], ko[b, 0]) and np.array_equal(inputs.to_oracle_array(vv)[b, 0], vo[b, 0])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("n_wg", [2, 5, 40, 3000])
+def test_other_grid_sizes(kb, dtype, n_wg):
+    """A handful of workgroups (every share holds several sequences and parts of others) and more
+    workgroups than the line has octets (single-octet shares, idle workgroups, one sequence merged
+    from more than a hundred parts)."""
+    Hq, Hkv, d, cap = 8, 2, 128, 9000
+    lens = np.array([9000, 4500, 31, 0, 8193], np.int32)
+    share = np.array([0, 0], np.int32)
+    assert kb.lib().kvs_testing_set_decode_workgroups(n_wg) == kb.KVS_OK
+    try:
+        case = Case(kb, 2, Hq, Hkv, d, len(lens), dtype, cap, share, paged=True, seed=109)
+        _decode_and_check(kb, case, 1, lens)
+        _decode_and_check(kb, case, 0, lens[::-1].copy())
+    finally:
+        assert kb.lib().kvs_testing_set_decode_workgroups(0) == kb.KVS_OK
