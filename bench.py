@@ -187,6 +187,70 @@ def bench_distance(args, torch, kb, inputs, dev):
     print(json.dumps(line))
 
 
+def bench_similarity(args, torch, kb, inputs, dev):
+    """Similarity test of the strategy search: last-layer hidden states of two models on the calibration
+    set, 30 sentences x 64 tokens x hidden 5120 (the Llama-2-13B shape), bf16; a step = one
+    kvs_avg_cos_sim call (both readings are timed; the line reports the paper text's: mean first).
+    A few tens of MB per call: the launch is short against its own start and end, so the line also
+    carries a calibration set of 480 sentences of the same shape."""
+    hidden, tokens = 5120, 64
+    N = tokens * hidden
+    line = None
+    extra = {}
+    for S in (30, 480):
+        a = inputs.normal((S, N), 11, S, 0).to(dev)
+        b = (a.float() + 0.5 * inputs.normal((S, N), 11, S, 1, dtype="f32").to(dev)).bfloat16()
+        ws = torch.zeros(kb.lib().kvs_cos_sim_workspace_bytes(S), dtype=torch.uint8, device=dev)
+        res = {}
+        for mode in (0, 1):
+            out = [None]
+
+            def run():
+                out[0] = kb.kvs_avg_cos_sim(a, b, mode, workspace=ws)
+
+            # a call is a few microseconds of GPU time, less than one call through the interpreter:
+            # sixteen calls are recorded into a HIP graph (kernel nodes only) and the replays are timed
+            run()
+            torch.cuda.synchronize()
+            eager = float(out[0].item())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for _ in range(16):
+                    run()
+            us = _event_time_us(torch, graph.replay, args.steps, args.warmup) / 16
+            if float(out[0].item()) != eager:
+                raise SystemExit("graph replays gave another similarity than the eager call")
+            res[mode] = (us, eager)
+        nbytes = 2 * S * N * 2
+        if S == 30:
+            us, got = res[0]
+            achieved = nbytes / us / 1e3
+            line = {
+                "metric": "calibration similarity test, hidden-state bytes/s", "value": round(achieved, 1), "unit": "GB/s",
+                "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us * 1e-3, 5),
+                "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                "config": {"workload": "calibration similarity, 30 sentences x 64 tokens x hidden 5120", "sentences": S,
+                           "N": N, "reading": "cosine of the sentence-averaged vectors"},
+                "roofline": {"bound": "hbm", "kernel": "cos_sim_kernel<bf16>", "achieved": round(achieved, 1),
+                             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                             "traffic": None, "launch_us": round(us, 2), "algorithmic_bytes": nbytes},
+                "per_sentence_reading_us": round(res[1][0], 2)}
+            if not args.no_cpu_baseline:
+                from oracle.similarity import avg_cos_sim
+                oa, ob = inputs.to_oracle_array(a.cpu()), inputs.to_oracle_array(b.cpu())
+                c0 = time.perf_counter()
+                want = [avg_cos_sim(oa, ob, m_) for m_ in (0, 1)]
+                cpu_s = (time.perf_counter() - c0) / 2
+                line["cpu_baseline"] = {"value": round(nbytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                        "sample": f"fp64 numpy oracle on the same input, mean of the two readings: {cpu_s:.3f} s"}
+                line["parity_abs_error"] = {"mean_first": abs(res[0][1] - want[0]), "per_sentence": abs(res[1][1] - want[1])}
+        else:
+            extra = {"sentences": S, "mean_first_us": round(res[0][0], 2), "per_sentence_us": round(res[1][0], 2),
+                     "mean_first_gbps": round(nbytes / res[0][0] / 1e3, 1), "per_sentence_gbps": round(nbytes / res[1][0] / 1e3, 1)}
+    line["larger_set"] = extra
+    print(json.dumps(line))
+
+
 def bench_project(args, torch, kb, inputs, dev):
     """Fused K/V projection + rotary embedding + append, Llama-3-8B shape (hidden 4096, 8 kv heads
     x 128): the per-layer work that sharing removes for recipient layers.  One new row per
@@ -338,11 +402,11 @@ def main():
                     help="--mode prefill: rows per sequence in the chunk (default: the workload's 64)")
     ap.add_argument("--project-rows", type=int, default=1,
                     help="--mode project: new rows per sequence (1 = decode step, more = prefill chunk)")
-    ap.add_argument("--mode", choices=["decode", "prefill", "distance", "project", "sparse"], default="decode",
+    ap.add_argument("--mode", choices=["decode", "prefill", "distance", "project", "sparse", "similarity"], default="decode",
                     help="decode (default): the whole decode step, the headline metric.  prefill: the 64-row "
                          "causal chunk of the llama2-13b workload.  distance: the 48-layer calibration matrix. "
                          "project: the fused K/V projection (see --project-rows).  sparse: decode attention over "
-                         "sparsified slots.  All but decode time the other kernels of the path, one JSON line each.")
+                         "sparsified slots.  similarity: the calibration similarity test.  All but decode time the other kernels of the path, one JSON line each.")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (torch) so that a counter trace of this "
                          "command contains a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -366,6 +430,8 @@ def main():
         return bench_project(args, torch, kb, inputs, dev)
     if args.mode == "sparse":
         return bench_sparse(args, torch, kb, inputs, dev)
+    if args.mode == "similarity":
+        return bench_similarity(args, torch, kb, inputs, dev)
     w = inputs.WORKLOADS[args.workload]
 
     share = inputs.make_share_map(w.L, w.n_shared, 1, fixed=w.fixed_map)

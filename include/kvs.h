@@ -333,7 +333,9 @@ size_t kvs_distance_workspace_bytes(int L);
  *   mode 1: average over the sentences of the per-sentence cosine (the procedure's name).
  * A zero vector contributes a cosine of 0.  The caller compares the result with the
  * threshold T inside its kvs_accept_fn (keep the pair iff similarity > T).
- * workspace >= kvs_cos_sim_workspace_bytes(S).
+ * workspace: device, >= kvs_cos_sim_workspace_bytes(S), zero-filled once by the caller (it starts
+ * with an arrival counter that every call leaves at zero, followed by partial sums); calls that
+ * share it must not overlap in time.  One kernel launch.
  */
 int kvs_avg_cos_sim(const void* hidden_shared, const void* hidden_original, int S, size_t N,
                     int dtype, int mode, float* similarity,

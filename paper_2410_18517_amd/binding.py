@@ -413,7 +413,7 @@ def kvs_avg_cos_sim(hidden_shared, hidden_original, mode=0, workspace=None):
     if need == 0:
         raise KvsError(KVS_ERR_INVALID_ARG, last_error())
     if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
+        workspace = torch.zeros(need, dtype=torch.uint8, device=a.device)
     out = torch.empty(1, dtype=torch.float32, device=a.device)
     _check(lib().kvs_avg_cos_sim(a.data_ptr(), b.data_ptr(), S, N, KVS_BF16 if a.dtype == torch.bfloat16 else KVS_F32,
                                  int(mode), out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
