@@ -11,7 +11,8 @@ import numpy as np
 import torch  # imported before the library so both use the same HIP runtime
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libkvs.so")
+# KVS_LIBRARY names another build of the same library (the sanitizer run of tests/sanitize_cpu.py)
+LIB_PATH = os.environ.get("KVS_LIBRARY") or os.path.join(_HERE, "libkvs.so")
 
 KVS_OK, KVS_NOOP = 0, 1
 KVS_ERR_INVALID_ARG, KVS_ERR_BAD_MAP, KVS_ERR_CAPACITY = -1, -2, -3
