@@ -169,3 +169,42 @@ def test_decode_step_full_size_sampled(kb, name):
                                         [None if a is None else a[b:b + 1] for a in V],
                                         inputs.to_oracle_array(q[b:b + 1]), lens[b:b + 1])
             assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, (layer, b)
+
+
+def test_projection_full_size_sampled(kb):
+    """The fused K/V projection at the shape bench.py times for a prefill chunk: 4 x 2048 rows,
+    hidden 4096, 8 kv heads of 128 (64 staged contraction steps, the two-heads-per-workgroup
+    kernel), rotary embedding, a permuted page table.  The fp64 oracle projects 96 sampled rows
+    (first and last rows of tiles and sequences among them) and every stored channel of those rows
+    is held to one bf16 unit of it."""
+    from oracle.projection import project_kv
+    Hq, Hkv, d, hidden, B, T = 32, 8, 128, 4096, 4, 2048
+    cap = 4096
+    share = np.array([0, 1, 1], np.int32)
+    table = inputs.make_block_table(B, cap // 16, B * cap // 16, 67)
+    store = kb.KVStore(share, Hq, Hkv, d, "bf16", B * cap // 16, cap // 16, block_table=table, zero_fill=True)
+    x = (inputs.normal((B, T, hidden), 67, 0, dtype="f32") / 4).to(torch.bfloat16)
+    wk = (inputs.normal((Hkv * d, hidden), 67, 1, dtype="f32") / np.sqrt(hidden)).to(torch.bfloat16)
+    wv = (inputs.normal((Hkv * d, hidden), 67, 2, dtype="f32") / np.sqrt(hidden)).to(torch.bfloat16)
+    inv = 10000.0 ** (-np.arange(d // 2, dtype=np.float64) * 2.0 / d)
+    ang = np.outer(np.arange(cap, dtype=np.float64), inv)
+    cos, sin = np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+    start = np.array([0, 2048, 1000, 37], np.int32)
+    assert kb.kvs_project_append_kv(store, 1, x.cuda(), wk.cuda(), wv.cuda(), start, torch.from_numpy(cos).cuda(),
+                                    torch.from_numpy(sin).cuda()) == kb.KVS_OK
+    rng = np.random.default_rng(67)
+    rows = sorted(set([0, 1, 255, 256, 2047] + rng.integers(0, T, size=19).tolist()))
+    xo, wko, wvo = inputs.to_oracle_array(x), inputs.to_oracle_array(wk), inputs.to_oracle_array(wv)
+    checked = 0
+    for b in range(B):
+        k_all, v_all = kb.kvs_gather_kv(store, 2, int(start[b]), T, B)        # through the recipient layer
+        for i in rows:
+            want_k, want_v = project_kv(xo[b:b + 1, i:i + 1], wko, wvo, Hkv, d, start[b:b + 1] + i, cos, sin)
+            for got, want in ((k_all[b, i], want_k[0, 0]), (v_all[b, i], want_v[0, 0])):
+                got = got.float().cpu().numpy().astype(np.float64)
+                floor = 1e-2 * np.sqrt((want ** 2).mean())
+                assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.maximum(np.abs(want), floor)), (b, i)
+                checked += got.size
+    assert checked >= 96 * 2 * Hkv * d
+    k0, _ = kb.kvs_gather_kv(store, 0, 0, 64, B)                              # another layer's slot: untouched
+    assert float(k0.float().abs().max()) == 0.0
