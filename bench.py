@@ -34,11 +34,16 @@ def algorithmic_bytes_per_launch(w, seq_lens, store_dtype=None):
     return kv + qo + table
 
 
-def recorded_traffic(workload):
-    """HBM bytes per launch from the committed counter summary, or None when there is none for this
-    workload or the kernel source has changed since the counters were taken."""
+DECODE_SOURCES = ("kvs_decode.hip", "kvs_attn_tiles.h", "kvs_flat_plan.h", "kvs_device.h")
+PREFILL_SOURCES = ("kvs_attention.hip", "kvs_attn_tiles.h", "kvs_device.h")
+DISTANCE_SOURCES = ("kvs_distance.hip",)
+
+
+def recorded_traffic(name, sources):
+    """HBM bytes per launch from the committed counter summary profiles/<name>.traffic.txt, or None
+    when there is none or the kernel's sources have changed since the counters were taken."""
     import hashlib
-    path = os.path.join(ROOT, "profiles", f"attn_bf16_decode_{workload}.traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"{name}.traffic.txt")
     if not os.path.exists(path):
         return None
     rec = {}
@@ -47,11 +52,21 @@ def recorded_traffic(workload):
             k, v = line.split("=", 1)
             rec[k.strip()] = v.strip()
     digest = hashlib.sha256()
-    for name in ("kvs_attention.hip", "kvs_device.h"):           # the decode kernel and the helpers it inlines
-        digest.update(open(os.path.join(ROOT, "paper_2410_18517_amd", "csrc", name), "rb").read())
+    for src in sources:                                          # the kernel and the headers it inlines
+        digest.update(open(os.path.join(ROOT, "paper_2410_18517_amd", "csrc", src), "rb").read())
     if rec.get("kernel_source_sha256") != digest.hexdigest():
         return None
     return int(rec["traffic_bytes_per_launch"])
+
+
+def traffic_probe(torch, dev):
+    """One plain 1 GiB device copy (torch): a kernel of known traffic in the same counter trace, to
+    scale FETCH_SIZE / WRITE_SIZE by."""
+    src = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)      # 1 GiB read, 1 GiB written
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
 
 
 def _event_time_us(torch, fn, steps, warmup):
@@ -105,6 +120,8 @@ def bench_prefill(args, torch, kb, inputs, dev):
         kb.kvs_append_kv(store, it[0] % n_layers, k_new, k_new, start)
         it[0] += 1
 
+    if args.traffic_probe:
+        traffic_probe(torch, dev)
     attn_us = _event_time_us(torch, attn, args.steps, args.warmup)
     append_us = _event_time_us(torch, append, args.steps, args.warmup)
     kv_bytes = w.B * w.context * w.Hkv * w.d * 2 * (1 if store_dtype == "fp8" else 2) + w.B * T * w.Hq * w.d * (2 + 4)
@@ -130,7 +147,8 @@ def bench_prefill(args, torch, kb, inputs, dev):
         roof = {"bound": "mfma", "kernel": kernel, "achieved": round(flops / attn_us / 1e6, 1),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(flops / attn_us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)}
-    roof.update({"traffic": None, "launch_us": round(attn_us, 2), "algorithmic_bytes": kv_bytes, "algorithmic_flops": flops})
+    traffic = recorded_traffic("attn_bf16_prefill_llama2-13b", PREFILL_SOURCES) if T == w.prefill_rows and store_dtype == "bf16" else None
+    roof.update({"traffic": traffic, "launch_us": round(attn_us, 2), "algorithmic_bytes": kv_bytes, "algorithmic_flops": flops})
     print(json.dumps({
         "metric": "causal prefill chunk attention, rows/s", "value": round(w.B * T / (attn_us * 1e-6), 1),
         "unit": "query rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -157,6 +175,8 @@ def bench_distance(args, torch, kb, inputs, dev):
     def run():
         outs[0] = kb.kvs_layer_distance(kv, workspace=ws)
 
+    if args.traffic_probe:
+        traffic_probe(torch, dev)
     us = _event_time_us(torch, run, args.steps, args.warmup)
     torch.cuda.synchronize()
     got = [o.cpu().numpy().astype(np.float64) for o in outs[0]]     # the last timed launch's own output
@@ -169,7 +189,8 @@ def bench_distance(args, torch, kb, inputs, dev):
         "config": {"workload": "calibration 30 x 48 layers x (8 x 512 x 128), structured", "samples": S, "layers": L, "N": N},
         "roofline": {"bound": "hbm", "kernel": "distance_partial_kernel<bf16, 256-position chunks> + distance_final_kernel",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "launch_us": round(us, 2),
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": recorded_traffic("distance_calibration_48_layers", DISTANCE_SOURCES), "launch_us": round(us, 2),
                      "algorithmic_bytes": nbytes}}
     if not args.no_cpu_baseline:
         print("GPU part done, running the CPU oracle", file=sys.stderr, flush=True)
@@ -368,7 +389,7 @@ def bench_sparse(args, torch, kb, inputs, dev):
         "config": {"workload": "llama3-8b-32k, 80 % of the tokens kept per kv head", "batch": w.B, "q_heads": w.Hq,
                    "kv_heads": w.Hkv, "head_dim": w.d, "context": w.context, "kept_per_head": n_keep},
         "compact_ms_per_layer": round(float(np.mean(compact_ms)), 3),
-        "roofline": {"bound": "hbm", "kernel": "attn_bf16_kernel<128,1> (per-head lengths)", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "attn_bf16_kernel<128,1,4,false> (per-head lengths)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "launch_us": round(us, 2), "algorithmic_bytes": nbytes}}
     if not args.no_cpu_baseline:
@@ -487,11 +508,7 @@ def main():
                 kb.kvs_decode_step(store, l, q[l], k_new, v_new, lens_dev, out=out[l], workspace=ws)
 
     if args.traffic_probe:
-        src = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)      # 1 GiB read, 1 GiB written
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        traffic_probe(torch, dev)
 
     print("store filled, timing", file=sys.stderr, flush=True)
     if args.graph:
@@ -531,11 +548,13 @@ def main():
     launch_ms = float(np.mean([a.elapsed_time(b) for a, b in launch_ms])) / w.L
     alg_bytes = algorithmic_bytes_per_launch(w, seq_lens, store_dtype)
     achieved = alg_bytes / (launch_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "attn_bf16_kernel<128,1%s> (one kvs_decode_attention launch)" % (
-                    ", fp8 pages" if store_dtype == "fp8" else ""),
+    kernel = ("attn_f32_kernel" if store_dtype == "f32" else
+              "attn_decode_flat_kernel<%d,%s> (one kvs_decode_attention launch)" % (w.d, "fp8 pages" if store_dtype == "fp8" else "bf16 pages"))
+    roofline = {"bound": "hbm", "kernel": kernel,
                 "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": recorded_traffic(w.name) if store_dtype == w.dtype and not args.seq_lens else None,
+                "traffic": None if args.seq_lens else recorded_traffic(
+                    f"attn_{'fp8' if store_dtype == 'fp8' else 'bf16'}_decode_{w.name}", DECODE_SOURCES),
                 "launch_us": round(launch_ms * 1e3, 2),
                 "algorithmic_bytes": alg_bytes}
 
