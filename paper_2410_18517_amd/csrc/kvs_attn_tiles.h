@@ -291,6 +291,70 @@ __device__ __forceinline__ void pair_softmax(const floatx4 (&sa)[NT], const floa
     }
 }
 
+// The same update for kernels bound by their own arithmetic (prefill with many query columns),
+// where every vector instruction counts: on this part the vector instructions of a wavefront do
+// not run beside the matrix instructions of the other wavefront of its SIMD, the two add up.
+// The reference m starts at kNoReference, finite and far below any score, instead of minus
+// infinity, so no case needs a guard (the first score a column sees overflows its weight, which
+// moves the reference to that pair's maximum); the weights are formed against the reference first,
+// and whether it has to move is read off their sum, which the update needs anyway: a lane's eight
+// weights sum to more than 2^kRefSlack only if one of them exceeds 2^(kRefSlack - 3), and a column
+// whose maximum is that far above the reference moves (then its weights are formed again, all at
+// most 1).  The maxima are computed only then.
+constexpr float kMoveAt = kRefSlack - 3.5f;      // log2 units above the reference from which a column moves once a sum trips
+constexpr float kNoReference = -1e30f;
+
+template <int D, int NT>
+__device__ __forceinline__ void pair_softmax_by_sum(const floatx4 (&sa)[NT], const floatx4 (&sb)[NT], bool have_b, int tok_a,
+                                                    int tok_b, int n_min, const int (&n_col)[NT], float (&m)[NT],
+                                                    float (&l)[NT], floatx4 (&o)[NT][D / 16], int quad, float scale_log2,
+                                                    bf16x8 (&pf)[NT])
+{
+    constexpr int DT = D / 16;
+    const bool need_mask = !have_b || tok_b + kPageTokens > n_min || tok_a + kPageTokens > n_min;
+    const float sum_limit = __builtin_amdgcn_exp2f(kRefSlack);
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        float z[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            z[i] = sa[ct][i];
+            z[4 + i] = sb[ct][i];
+        }
+        if (need_mask) {
+            const int ta = tok_a + quad * 4, tb = tok_b + quad * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                z[i] = (ta + i < n_col[ct]) ? z[i] : -INFINITY;
+                z[4 + i] = (have_b && tb + i < n_col[ct]) ? z[4 + i] : -INFINITY;
+            }
+        }
+        float p[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(z[i], scale_log2, -m[ct]));
+        float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        if (__any(!(ps <= sum_limit))) {                     // some weight is too large (or overflowed): rare
+            const float lane_max = scale_log2 * fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
+                                                      fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+            const float mx = column_max(lane_max);           // minus infinity while the column sees nothing
+            const bool up = mx > m[ct] + kMoveAt;
+            const float m_new = up ? mx : m[ct];
+            const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_new);   // 1 in columns that keep their reference
+            l[ct] *= alpha;
+#pragma unroll
+            for (int c = 0; c < DT; ++c) o[ct][c] *= alpha;
+            m[ct] = m_new;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(z[i], scale_log2, -m_new));
+            ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        }
+        l[ct] += ps;
+        const uint4 pw = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
+                                    pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+        pf[ct] = __builtin_bit_cast(bf16x8, pw);
+    }
+}
+
 // o += V^T . P^T.  Tokens past the stored length hold whatever the allocation held:
 // their values are cleared first, so that a zero probability cannot meet a NaN.
 template <int D, int NT>

@@ -40,6 +40,8 @@ struct AttnArgs {
     int32_t n_items;        //   3 = the kernel of kvs_decode.hip: n_items workgroups share the launch's pages out by
                             //   tokens; partials one record per (workgroup + segment, head of the group)
     int32_t wide_cols;      // prefill: 0 = the page-splitting kernel, else columns per workgroup of the shared-page kernel (64, 128, 256)
+    int32_t col_blocks;     // set by the launch: > 0 = the shared-page kernel runs on a 1-D grid dealt to the XCDs, with this
+                            //   many column blocks per (sequence, kv head); 0 = grid (kv head, sequence, blocks x splits)
 };
 
 struct CopyArgs {

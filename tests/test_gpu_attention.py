@@ -300,15 +300,16 @@ def test_shared_page_prefill_kernels(kb, d, Hq, Hkv, B, T_new):
     q = case.q(1, rows=T_new)
     got = kb.kvs_prefill_attention(case.store, 1, q.cuda(), start).cpu().numpy()
     assert np.isfinite(got).all()
+    # the same rows as a short chunk take the page-splitting kernel: both kernels are held to the
+    # oracle (not to each other: two results within tol of a third are only within 2 tol of each other)
+    tail = 8
+    short = kb.kvs_prefill_attention(case.store, 1, q[:, -tail:].contiguous().cuda(), start + (T_new - tail)).cpu().numpy()
+    assert np.isfinite(short).all()
     for b in (0, B // 2, B - 1):
         want = orc.shared_attention(1, share, [case.K[0][b:b + 1], None], [case.V[0][b:b + 1], None],
                                     inputs.to_oracle_array(q[b:b + 1]), start[b:b + 1])
         assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, b
-    # a row's output must not depend on which kernel computed it: the same rows as a short chunk
-    # (which takes the page-splitting kernel) agree to rounding
-    tail = 8
-    short = kb.kvs_prefill_attention(case.store, 1, q[:, -tail:].contiguous().cuda(), start + (T_new - tail)).cpu().numpy()
-    assert rel_l2_rows(short, got[:, -tail:].astype(np.float64)).max() <= REL_L2_ATTENTION
+        assert rel_l2_rows(short[b:b + 1], want[:, -tail:]).max() <= REL_L2_ATTENTION, b
 
 
 # Few (sequence, kv head) pairs: the shared-page kernels split the context over workgroups too, and
