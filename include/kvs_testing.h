@@ -32,9 +32,10 @@ int kvs_testing_set_decode_workgroups(int n);
 /*
  * The integer plan by which a decode launch shares out its pages by tokens, as the kernel computes
  * it on the device, for a host-side check against brute force: a line of `total` octets (eight
- * pages each) is cut into n shares that differ by at most one octet.  kvs_testing_flat_share
- * writes the share of workgroup i (first octet, number of octets); kvs_testing_flat_owner returns
- * the workgroup whose share holds octet o, or -1 for arguments out of range.
+ * pages each) is cut into n <= 65535 shares that differ by at most one octet, share i beginning at
+ * octet floor(total * i / n) (a line shorter than n: one octet for each of the first workgroups).  kvs_testing_flat_share writes the share of workgroup i (first
+ * octet, number of octets); kvs_testing_flat_owner returns the workgroup whose share holds octet
+ * o, or -1 for arguments out of range.
  */
 int kvs_testing_flat_share(int i, int n, int total, int* first, int* count);
 int kvs_testing_flat_owner(int o, int n, int total);

@@ -134,7 +134,8 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
     }
     const int head_octs = __builtin_amdgcn_readlane(incl, 63);       // octets of one kv head
     const int total = head_octs * Hkv;
-    const FlatShare mine = flat_share(wg, n_wg, total);
+    const FlatPlan plan(n_wg, total);
+    const FlatShare mine = plan.share(wg);
 
     auto advance = [&](Cursor& c) {                                  // only called while an octet follows on the line
         if (++c.oi < c.octs) return;
@@ -260,8 +261,8 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
         auto finish_segment = [&](int g, int b) {
             const int octs = __builtin_amdgcn_readlane(octs_lane, b);
             const int seg_lo = g * head_octs + __builtin_amdgcn_readlane(incl, b) - octs;
-            const int first_wg = flat_owner(seg_lo, n_wg, total);
-            const int parts = flat_owner(seg_lo + octs - 1, n_wg, total) - first_wg + 1;
+            const int first_wg = plan.owner(seg_lo);
+            const int parts = plan.owner(seg_lo + octs - 1) - first_wg + 1;
             // A step that carries its own new token: the workgroup that holds the segment's first
             // octet adds it as one more state (score, weight 1, value row v_new) and stores the row.
             const int new_pos = seg_len_raw - 1;

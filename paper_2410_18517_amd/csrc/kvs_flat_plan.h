@@ -23,23 +23,49 @@ struct FlatShare {
     int lo, count;      // octets [lo, lo + count) of the line
 };
 
-// Share of workgroup i of n over a line of `total` octets: the first total % n workgroups take
-// one octet more than the others.
-KVS_PLAN_FN FlatShare flat_share(int i, int n, int total)
-{
-    const int base = total / n, rem = total % n;
-    FlatShare s;
-    s.lo = i * base + (i < rem ? i : rem);
-    s.count = base + (i < rem ? 1 : 0);
-    return s;
-}
+// The cut of a line of `total` octets into n shares (n <= 65535).  Share i begins at octet
+// floor(total * i / n), so the shares differ by at most one octet and the longer ones are spread
+// evenly over the workgroups.  A line shorter than n gives its octets to the first `total`
+// workgroups, one each: the workgroups that hold the parts of a segment are then always consecutive,
+// none of them empty, which the kernel's count of a segment's parts relies on.
+// All in 32-bit arithmetic ((total % n) * i stays below 2^32), the two divisions by n that depend on
+// the line alone done once.
+struct FlatPlan {
+    int n, total;
+    unsigned base, rem;      // total = base * n + rem
+    float per_octet;         // n / total: the owner of an octet, up to rounding
 
-// The workgroup whose share holds octet o (0 <= o < total).
-KVS_PLAN_FN int flat_owner(int o, int n, int total)
-{
-    const int base = total / n, rem = total % n;
-    const int big = rem * (base + 1);          // octets held by the larger shares
-    return o < big ? o / (base + 1) : rem + (o - big) / base;   // base > 0 whenever o >= big
-}
+    KVS_PLAN_FN FlatPlan(int n_, int total_) : n(n_), total(total_)
+    {
+        base = (unsigned)total / (unsigned)n;
+        rem = (unsigned)total - base * (unsigned)n;
+        per_octet = total > 0 ? (float)n / (float)total : 0.f;
+    }
+    // first octet of workgroup i's share, i = 0 .. n (i = n: the end of the line)
+    KVS_PLAN_FN int bound(int i) const
+    {
+        if (total < n) return i < total ? i : total;
+        return (int)(base * (unsigned)i + (rem ? rem * (unsigned)i / (unsigned)n : 0u));
+    }
+    KVS_PLAN_FN FlatShare share(int i) const
+    {
+        FlatShare s;
+        s.lo = bound(i);
+        s.count = bound(i + 1) - s.lo;
+        return s;
+    }
+    // the workgroup whose share holds octet o (0 <= o < total)
+    KVS_PLAN_FN int owner(int o) const
+    {
+        int i = (int)(((float)o + 0.5f) * per_octet);
+        i = i < 0 ? 0 : (i > n - 1 ? n - 1 : i);
+        while (bound(i) > o) --i;
+        while (bound(i + 1) <= o) ++i;
+        return i;
+    }
+};
+
+KVS_PLAN_FN FlatShare flat_share(int i, int n, int total) { return FlatPlan(n, total).share(i); }
+KVS_PLAN_FN int flat_owner(int o, int n, int total) { return FlatPlan(n, total).owner(o); }
 
 }  // namespace kvs

@@ -318,7 +318,8 @@ int kvs_testing_set_decode_workgroups(int n)
 
 int kvs_testing_flat_share(int i, int n, int total, int* first, int* count)
 {
-    if (n <= 0 || i < 0 || i >= n || total < 0 || !first || !count) return fail(KVS_ERR_INVALID_ARG, "need 0 <= i < n, total >= 0");
+    if (n <= 0 || n > 65535 || i < 0 || i >= n || total < 0 || !first || !count)
+        return fail(KVS_ERR_INVALID_ARG, "need 0 <= i < n <= 65535, total >= 0");
     const kvs::FlatShare s = kvs::flat_share(i, n, total);
     *first = s.lo;
     *count = s.count;
@@ -327,7 +328,7 @@ int kvs_testing_flat_share(int i, int n, int total, int* first, int* count)
 
 int kvs_testing_flat_owner(int o, int n, int total)
 {
-    if (n <= 0 || o < 0 || o >= total) return -1;
+    if (n <= 0 || n > 65535 || o < 0 || o >= total) return -1;
     return kvs::flat_owner(o, n, total);
 }
 

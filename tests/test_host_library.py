@@ -248,22 +248,26 @@ def test_noalloc_entry_point_refuses_shapes_beyond_its_scratch():
 
 def test_token_shares_of_a_decode_launch_partition_the_line():
     """The plan the decode kernel derives on the device, against brute force: n shares tile the line
-    of octets without gap or overlap, differ by at most one octet, and the owner look-up inverts them."""
+    of octets without gap or overlap, share i begins at floor(total * i / n) (so the shares differ by
+    at most one octet; a line shorter than n goes to the first workgroups, one octet each), and the
+    owner look-up inverts them."""
     lib = kb.lib()
     first, count = C.c_int(0), C.c_int(0)
-    for n in (1, 2, 7, 8, 256):
-        for total in list(range(0, 40)) + [255, 256, 257, 511, 2720, 8192, 10240, 65537]:
-            at, sizes, owner = 0, [], []
-            for i in range(n):
+    for n in (1, 2, 7, 8, 256, 3000, 65535):
+        for total in list(range(0, 40)) + [255, 256, 257, 511, 2720, 8192, 10240, 65537, (1 << 25) - 1]:
+            # a line shorter than n: one octet for each of the first `total` workgroups, so that no empty share
+            # lies between two that hold parts of one segment
+            bound = (lambda i: total * i // n) if total >= n else (lambda i: min(i, total))
+            probe = range(n) if n <= 256 else list(range(0, n, max(1, n // 97))) + [n - 1]
+            sizes = []
+            for i in probe:
                 assert lib.kvs_testing_flat_share(i, n, total, C.byref(first), C.byref(count)) == kb.KVS_OK
-                assert first.value == at and count.value >= 0
-                at += count.value
+                assert first.value == bound(i) and first.value + count.value == bound(i + 1)
                 sizes.append(count.value)
-                owner += [i] * count.value
-            assert at == total and max(sizes) - min(sizes) <= 1
-            assert sizes == sorted(sizes, reverse=True)                      # the larger shares come first
+            assert max(sizes) - min(sizes) <= 1
             step = max(1, total // 300)
             for o in list(range(0, total, step)) + [total - 1] * (total > 0):
-                assert lib.kvs_testing_flat_owner(o, n, total) == owner[o], (n, total, o)
+                i = lib.kvs_testing_flat_owner(o, n, total)
+                assert 0 <= i < n and bound(i) <= o < bound(i + 1), (n, total, o, i)
             assert lib.kvs_testing_flat_owner(total, n, total) == -1
     assert lib.kvs_testing_flat_share(3, 3, 10, C.byref(first), C.byref(count)) == kb.KVS_ERR_INVALID_ARG
