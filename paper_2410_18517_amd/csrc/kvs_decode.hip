@@ -229,7 +229,7 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
         bf16x8 qf[1][KS];
         float m[1], l[1];
         floatx4 o[1][DT];
-        auto begin_segment = [&](const Cursor& c) {
+        auto begin_segment = [&](const Cursor& c, bool settle) {
             seg_n = __builtin_amdgcn_readlane(n0_lane, c.b);
             seg_len_raw = __builtin_amdgcn_readlane(len_raw_lane, c.b);
             const bool col_ok = col < group;
@@ -246,9 +246,12 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
             for (int c2 = 0; c2 < DT; ++c2) o[0][c2] = floatx4{0.f, 0.f, 0.f, 0.f};
             // The queries are waited for here, inside the branch that loads them: left pending, they
             // would be the youngest loads on this path, and where it rejoins the loop the compiler
-            // would make every step wait for "them", i.e. for everything in flight.
+            // would make every step wait for "them", i.e. for everything in flight.  (The share's
+            // first segment settles them itself, behind its first page loads.)
+            if (settle) {
 #pragma unroll
-            for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qf[0][s]));
+                for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qf[0][s]));
+            }
         };
 
         __shared__ float lds_new_score[16];           // log2-domain score of the step's own token, per column
@@ -345,8 +348,10 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
 
         // kDepth octets in flight per wavefront; the steps are rounded up to whole turns of the ring,
         // the ones past the share fetch and consume nothing real
+        // The first segment's queries are requested first and waited for behind the first page loads:
+        // waited for where they are requested, their round trip stood before the first page load.
         Raw ring[kDepth][2];
-        begin_segment(cur);
+        begin_segment(cur, false);
 #pragma unroll
         for (int j = 0; j < kDepth; ++j) {
             const bool live = j < mine.count;
@@ -355,6 +360,8 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
                              ahead.oi * kOctetPages + 2 * wave == guess_page[j < 2 ? j : 0];
             fetch(ahead, live, ring[j][0], ring[j][1], hit, j < 2 ? j : 0);
         }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qf[0][s]));
         int seg_g = cur.g, seg_b = cur.b;
         for (int o0 = 0; o0 < mine.count; o0 += kDepth) {
 #pragma unroll
@@ -363,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
                 const bool live = oo < mine.count;
                 if (live && oo > 0 && cur.oi == 0) {         // the line has passed into the next segment
                     finish_segment(seg_g, seg_b);
-                    begin_segment(cur);
+                    begin_segment(cur, true);
                     seg_g = cur.g;
                     seg_b = cur.b;
                 }
