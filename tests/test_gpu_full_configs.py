@@ -1,8 +1,8 @@
 """GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times
 (full batch, full store geometry, default split policy, permuted page table).  The store is
 allocated at full size; only the layers that are sampled (recipients, their donors and layer 0)
-are filled, since a layer's kernel touches no other slot.  The oracle checks sampled sequences,
-all heads, element by element."""
+are filled, since a layer's kernel touches no other slot.  For decode the oracle checks every
+sequence and head of the sampled layers, element by element; for prefill sampled sequences."""
 import numpy as np
 import pytest
 import torch
@@ -43,19 +43,17 @@ def test_decode_full_size_sampled(kb, name):
                 fill_layers=fill, spare_blocks=0)
     assert case.store.desc.n_slots == w.L - w.n_shared
     tol = 1e-5 if w.dtype == "f32" else REL_L2_ATTENTION
-    seqs = sorted(set([int(np.argmax(lens)), int(np.argmin(lens)), w.B // 2]))
     worst = 0.0
     for layer in layers:
         q = case.q(layer)
         got = kb.kvs_decode_attention(case.store, layer, q.cuda(), lens).cpu().numpy()
         assert np.isfinite(got).all()
-        for b in seqs:
-            want = orc.decode_attention(layer, share, _sub(case, case.K, b), _sub(case, case.V, b),
-                                        inputs.to_oracle_array(q[b:b + 1]), lens[b:b + 1])
-            err = rel_l2_rows(got[b:b + 1], want).max()
-            worst = max(worst, err)
-            assert err <= tol, (name, layer, b, err)
-    print(f"{name}: layers {layers}, sequences {seqs}, max rel L2 {worst:.2e}")
+        # every sequence and head of the launch (the oracle walks a whole layer of the largest workload in 0.2 s)
+        want = orc.decode_attention(layer, share, case.K, case.V, inputs.to_oracle_array(q), lens)
+        err = rel_l2_rows(got, want)
+        worst = max(worst, err.max())
+        assert err.max() <= tol, (name, layer, np.unravel_index(np.argmax(err), err.shape), err.max())
+    print(f"{name}: layers {layers}, all {w.B} sequences, max rel L2 {worst:.2e}")
 
 
 def test_prefill_full_size_sampled(kb):
