@@ -158,6 +158,40 @@ def test_decode_splits_follow_the_lengths(kb, dtype, kind, Hq, Hkv, B):
     assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
 
 
+# More than 64 sequences take the split kernel (the token-shared one keeps one sequence per lane): a
+# ragged batch with empty and full sequences, the plain call twice on one workspace and the decode
+# step that stores its own token.
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("Hq,Hkv,B,cap", [(12, 2, 65, 700), (8, 8, 128, 300), (6, 1, 300, 130)])
+def test_decode_more_than_64_sequences(kb, dtype, Hq, Hkv, B, cap):
+    d = 128
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, 2, Hq, Hkv, d, B, dtype, cap, share, paged=True, seed=113)
+    rng = np.random.default_rng(113)
+    lens = rng.integers(0, cap + 1, size=B).astype(np.int32)
+    lens[:5] = [cap, 0, 1, 16, 17]
+    q = case.q(1)
+    qo = inputs.to_oracle_array(q)
+    want = orc.decode_attention(1, share, case.K, case.V, qo, lens)
+    for _ in range(2):
+        got = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens).cpu().numpy()
+        assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
+    step_lens = np.maximum(lens, 1)
+    k_new = inputs.normal((B, 1, Hkv, d), 113, 700, dtype=case.row_dtype)
+    v_new = inputs.normal((B, 1, Hkv, d), 113, 701, dtype=case.row_dtype)
+    got = kb.kvs_decode_step(case.store, 0, q.cuda(), k_new.cuda(), v_new.cuda(), step_lens).cpu().numpy()
+    ko, vo = inputs.to_oracle_array(k_new), inputs.to_oracle_array(v_new)
+    if dtype == "fp8":
+        from helpers import stored_fp8
+        ko, vo = stored_fp8(ko), stored_fp8(vo)
+    assert orc.append_kv(0, share, case.K, case.V, ko, vo, step_lens - 1)
+    want = orc.decode_attention(0, share, case.K, case.V, qo, step_lens)
+    assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
+    # the rows the step stored are what a later call reads
+    again = kb.kvs_decode_attention(case.store, 1, q.cuda(), step_lens).cpu().numpy()
+    assert rel_l2_rows(again, want).max() <= REL_L2_ATTENTION
+
+
 # Seeded random shapes and length patterns through the plain decode call: batch sizes on either side
 # of 16 and 64 (how a launch reads the lengths), capacities off a multiple of the split sizes,
 # contiguous and paged stores.
