@@ -165,15 +165,16 @@ __global__ __launch_bounds__(256) void append_pages_bf16_kernel(CopyArgs a)
 
 // In-place compaction of a slot after token eviction: for every (sequence, kv head) the tokens
 // at the increasing positions keep_idx[0 .. count) move to positions 0 .. count.  A workgroup
-// owns one (kv head, sequence) and two of the 16-byte channel pieces of its rows (pieces never
-// interact, so they spread over workgroups) and walks the destination in chunks of 128 tokens:
-// thread (t, piece) loads its piece of K and of V of source token keep_idx[chunk + t], the
-// workgroup meets at a barrier, then the pieces are stored at chunk + t.  Because
+// owns one (kv head, sequence) and one of the 16-byte channel pieces of its rows (pieces never
+// interact, so they spread over workgroups) and walks the destination in chunks of 1024 tokens:
+// thread t loads the piece of K and of V of the source tokens keep_idx[chunk + t + 256 u],
+// u = 0 .. 3, the workgroup meets at a barrier, then the pieces are stored at chunk + t + 256 u.  Because
 // keep_idx[j] >= j, a chunk reads only positions at or behind its own start and writes only its
-// own 128 positions, so chunks never touch each other's data and one barrier per chunk is enough.
+// own positions, so chunks never touch each other's data and one barrier per chunk is enough.
 // kKind: the store's type code (0 fp32: a piece is 4 channels; 1 bf16, 2 fp8: 8 channels, whose keys
 // are one contiguous run in the page and whose values are eight separate elements).
-constexpr int kCompactTokens = 128;
+constexpr int kCompactTokens = 256;    // tokens one pass of the workgroup's threads covers
+constexpr int kCompactPasses = 4;      // passes per chunk: a thread moves this many tokens between two barriers
 template <int kKind>
 __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
 {
@@ -182,68 +183,81 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
     constexpr bool kBf16 = kKind == 1, kFp8 = kKind == 2;
     constexpr int per = kKind == 0 ? 4 : 8;
     const int g = blockIdx.x, b = blockIdx.y;
-    const int ch = blockIdx.z * 2 + (threadIdx.x & 1);         // this thread's piece of the row
-    const int tt = threadIdx.x >> 1;
+    const int ch = blockIdx.z;                                 // the workgroup's piece of the rows
+    const int tt = threadIdx.x;
     const int cap = st.max_blocks_per_seq * kPageTokens;
     int count = a.keep_count[b * st.Hkv + g];
     const int most = a.max_keep < cap ? a.max_keep : cap;
     count = count < 0 ? 0 : (count > most ? most : count);
     const int32_t* idx = a.keep_idx + ((size_t)b * st.Hkv + g) * a.max_keep;
     const int slot = resolve_slot(st);
-    for (int c0 = 0; c0 < count; c0 += kCompactTokens) {
-        const int j = c0 + tt;
-        const bool active = j < count && ch * per < D;
-        int src = active ? idx[j] : 0;
-        src = src < 0 ? 0 : (src >= cap ? cap - 1 : src);
-        const int sblk = block_of(st, b, src / kPageTokens);
-        const int dblk = block_of(st, b, (j < cap ? j : cap - 1) / kPageTokens);
-        const bool ok = active && sblk >= 0 && sblk < st.num_blocks && dblk >= 0 && dblk < st.num_blocks;
-        const int ts = src % kPageTokens, td = j % kPageTokens;
-        uint4 kreg = make_uint4(0, 0, 0, 0), vreg = make_uint4(0, 0, 0, 0);
-        if (ok) {
-            if (kBf16) {
-                const unsigned short* kp = static_cast<const unsigned short*>(st.pool) + page_offset(st, slot, sblk, g);
-                const unsigned short* vp = kp + kPageTokens * D;
-                kreg = *reinterpret_cast<const uint4*>(kp + k_index_bf16(ts, ch * 8));
-                unsigned w[4] = {0, 0, 0, 0};
+    // A chunk is kCompactPasses * kCompactTokens destination positions: the walk is a chain of
+    // dependent round trips (index, page-table entry, data, barrier, store), so the more tokens a
+    // thread has in flight per barrier the fewer such chains a (sequence, kv head) takes.
+    for (int c0 = 0; c0 < count; c0 += kCompactPasses * kCompactTokens) {
+        uint4 kreg[kCompactPasses], vreg[kCompactPasses];
+        int dblk[kCompactPasses];
+        bool ok[kCompactPasses];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) w[e >> 1] |= (unsigned)vp[v_index_bf16(ts, ch * 8 + e)] << ((e & 1) * 16);
-                vreg = make_uint4(w[0], w[1], w[2], w[3]);
-            } else if (kFp8) {
-                const unsigned char* kp = static_cast<const unsigned char*>(st.pool) + page_offset(st, slot, sblk, g);
-                const unsigned char* vp = kp + kPageTokens * D;
-                const uint2 k8 = *reinterpret_cast<const uint2*>(kp + k_index_fp8(ts, ch * 8));
-                kreg = make_uint4(k8.x, k8.y, 0, 0);
-                unsigned w[2] = {0, 0};
+        for (int u = 0; u < kCompactPasses; ++u) {
+            const int j = c0 + u * kCompactTokens + tt;
+            const bool active = j < count && ch * per < D;
+            int src = active ? idx[j] : 0;
+            src = src < 0 ? 0 : (src >= cap ? cap - 1 : src);
+            const int sblk = block_of(st, b, src / kPageTokens);
+            dblk[u] = block_of(st, b, (j < cap ? j : cap - 1) / kPageTokens);
+            ok[u] = active && sblk >= 0 && sblk < st.num_blocks && dblk[u] >= 0 && dblk[u] < st.num_blocks;
+            const int ts = src % kPageTokens;
+            kreg[u] = make_uint4(0, 0, 0, 0);
+            vreg[u] = make_uint4(0, 0, 0, 0);
+            if (ok[u]) {
+                if (kBf16) {
+                    const unsigned short* kp = static_cast<const unsigned short*>(st.pool) + page_offset(st, slot, sblk, g);
+                    const unsigned short* vp = kp + kPageTokens * D;
+                    kreg[u] = *reinterpret_cast<const uint4*>(kp + k_index_bf16(ts, ch * 8));
+                    unsigned w[4] = {0, 0, 0, 0};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) w[e >> 2] |= (unsigned)vp[v_index_fp8(ts, ch * 8 + e)] << ((e & 3) * 8);
-                vreg = make_uint4(w[0], w[1], 0, 0);
-            } else {
-                const float* kp = static_cast<const float*>(st.pool) + page_offset(st, slot, sblk, g) + (size_t)ts * D + ch * 4;
-                kreg = *reinterpret_cast<const uint4*>(kp);
-                vreg = *reinterpret_cast<const uint4*>(kp + kPageTokens * D);
+                    for (int e = 0; e < 8; ++e) w[e >> 1] |= (unsigned)vp[v_index_bf16(ts, ch * 8 + e)] << ((e & 1) * 16);
+                    vreg[u] = make_uint4(w[0], w[1], w[2], w[3]);
+                } else if (kFp8) {
+                    const unsigned char* kp = static_cast<const unsigned char*>(st.pool) + page_offset(st, slot, sblk, g);
+                    const unsigned char* vp = kp + kPageTokens * D;
+                    const uint2 k8 = *reinterpret_cast<const uint2*>(kp + k_index_fp8(ts, ch * 8));
+                    kreg[u] = make_uint4(k8.x, k8.y, 0, 0);
+                    unsigned w[2] = {0, 0};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) w[e >> 2] |= (unsigned)vp[v_index_fp8(ts, ch * 8 + e)] << ((e & 3) * 8);
+                    vreg[u] = make_uint4(w[0], w[1], 0, 0);
+                } else {
+                    const float* kp = static_cast<const float*>(st.pool) + page_offset(st, slot, sblk, g) + (size_t)ts * D + ch * 4;
+                    kreg[u] = *reinterpret_cast<const uint4*>(kp);
+                    vreg[u] = *reinterpret_cast<const uint4*>(kp + kPageTokens * D);
+                }
             }
         }
         __syncthreads();
-        if (ok) {
+#pragma unroll
+        for (int u = 0; u < kCompactPasses; ++u) {
+            if (!ok[u]) continue;
+            const int td = (c0 + u * kCompactTokens + tt) % kPageTokens;
             if (kBf16) {
-                unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, slot, dblk, g);
+                unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, slot, dblk[u], g);
                 unsigned short* vp = kp + kPageTokens * D;
-                *reinterpret_cast<uint4*>(kp + k_index_bf16(td, ch * 8)) = kreg;
-                const unsigned w[4] = {vreg.x, vreg.y, vreg.z, vreg.w};
+                *reinterpret_cast<uint4*>(kp + k_index_bf16(td, ch * 8)) = kreg[u];
+                const unsigned w[4] = {vreg[u].x, vreg[u].y, vreg[u].z, vreg[u].w};
 #pragma unroll
                 for (int e = 0; e < 8; ++e) vp[v_index_bf16(td, ch * 8 + e)] = (unsigned short)(w[e >> 1] >> ((e & 1) * 16));
             } else if (kFp8) {
-                unsigned char* kp = static_cast<unsigned char*>(st.pool) + page_offset(st, slot, dblk, g);
+                unsigned char* kp = static_cast<unsigned char*>(st.pool) + page_offset(st, slot, dblk[u], g);
                 unsigned char* vp = kp + kPageTokens * D;
-                *reinterpret_cast<uint2*>(kp + k_index_fp8(td, ch * 8)) = make_uint2(kreg.x, kreg.y);
-                const unsigned w[2] = {vreg.x, vreg.y};
+                *reinterpret_cast<uint2*>(kp + k_index_fp8(td, ch * 8)) = make_uint2(kreg[u].x, kreg[u].y);
+                const unsigned w[2] = {vreg[u].x, vreg[u].y};
 #pragma unroll
                 for (int e = 0; e < 8; ++e) vp[v_index_fp8(td, ch * 8 + e)] = (unsigned char)(w[e >> 2] >> ((e & 3) * 8));
             } else {
-                float* kp = static_cast<float*>(st.pool) + page_offset(st, slot, dblk, g) + (size_t)td * D + ch * 4;
-                *reinterpret_cast<uint4*>(kp) = kreg;
-                *reinterpret_cast<uint4*>(kp + kPageTokens * D) = vreg;
+                float* kp = static_cast<float*>(st.pool) + page_offset(st, slot, dblk[u], g) + (size_t)td * D + ch * 4;
+                *reinterpret_cast<uint4*>(kp) = kreg[u];
+                *reinterpret_cast<uint4*>(kp + kPageTokens * D) = vreg[u];
             }
         }
     }
@@ -305,7 +319,7 @@ int launch_append(const CopyArgs& a, void* stream)
 int launch_compact(const CompactArgs& a, void* stream)
 {
     const int pieces = a.st.head_dim / (a.st.dtype == 0 ? 4 : 8);
-    const dim3 grid(a.st.Hkv, a.B, (pieces + 1) / 2);
+    const dim3 grid(a.st.Hkv, a.B, pieces);
     if (a.st.dtype == 1)
         hipLaunchKernelGGL(compact_kernel<1>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
     else if (a.st.dtype == 2)
