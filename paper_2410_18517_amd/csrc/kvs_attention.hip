@@ -511,27 +511,32 @@ void attn_bf16_wide_kernel(AttnArgs a)
     const int quad = lane >> 4, col = lane & 15;
     // later column blocks see more keys (causality) and run longer: they are started first, so
     // that the launch does not end on its longest workgroups
-    int g, b, n_cblk, split, cblk;
-    if (a.col_blocks > 0) {
+    int g, b, n_cblk, split, turns = 1, cblk_first, cblk_second = 0;
+    if (NT == 2 && !kReadOnce && a.col_blocks > 0) {               // (only that variant is ever launched so)
         // 1-D grid, no context split: workgroup ids go round-robin over the eight XCDs, so ids
-        // 8 k + x, k = 0, 1, ... are consecutive on XCD x.  The column blocks of one (sequence, kv
-        // head) take consecutive k: they run side by side on one XCD, walk the same pages at about
-        // the same time, and all but the first find a page in that XCD's L2.
+        // 8 k + x, k = 0, 1, ... are consecutive on XCD x.  The workgroups of one (sequence, kv head)
+        // take consecutive k: they run side by side on one XCD, walk the same pages at about the same
+        // time, and all but the first find a page in that XCD's L2.  Either a workgroup per column
+        // block, or (col_paired, an even number of blocks) a workgroup takes the k-th longest block
+        // and then the k-th shortest, so that all workgroups of the launch do the same amount of work.
         n_cblk = a.col_blocks;
         split = 0;
+        const int per = a.col_paired ? n_cblk / 2 : n_cblk;        // workgroups per (sequence, kv head)
         const int xcd = (int)blockIdx.x % 8, k = (int)blockIdx.x / 8;
-        const int bg = (k / n_cblk) * 8 + xcd;
+        const int bg = (k / per) * 8 + xcd;
         if (bg >= a.B * st.Hkv) return;                            // padding of the last round
         g = bg % st.Hkv;
         b = bg / st.Hkv;
-        cblk = n_cblk - 1 - k % n_cblk;
+        cblk_first = n_cblk - 1 - k % per;
+        cblk_second = k % per;
+        turns = a.col_paired ? 2 : 1;
     } else {
         // grid (kv head, sequence, column blocks x context splits), the split index fastest
         g = blockIdx.x;
         b = blockIdx.y;
         n_cblk = gridDim.z / a.n_splits;
         split = (int)blockIdx.z % a.n_splits;
-        cblk = n_cblk - 1 - (int)blockIdx.z / a.n_splits;
+        cblk_first = n_cblk - 1 - (int)blockIdx.z / a.n_splits;
     }
     const int group = st.Hq / st.Hkv;
     const int ncols = a.T_new * group;
@@ -542,6 +547,8 @@ void attn_bf16_wide_kernel(AttnArgs a)
     n0 = n0 < 0 ? 0 : n0;
     if (n0 > cap - (a.T_new - 1)) n0 = cap - (a.T_new - 1);
 
+    for (int turn = 0; turn < turns; ++turn) {
+    const int cblk = turn == 0 ? cblk_first : cblk_second;
     // this lane's columns and their query fragments
     const int c_lo = cblk * kWideCols + wave * (NT * 16);
     size_t q_off[NT];
@@ -820,16 +827,22 @@ void attn_bf16_wide_kernel(AttnArgs a)
             if (quad == 0) publish_pair(part + D, lsum > 0.f ? m[ct] : -INFINITY, lsum)   /* saw nothing: as the merge expects it */;
         }
     }
-    if (live_splits <= 1) return;
-    if (!arrived_last(a.counters + ((size_t)b * st.Hkv + g) * n_cblk + cblk, live_splits)) return;
-    merge_splits<D>(a, b, g, cblk * kWideCols, kWideCols, ncols, group, live_splits, kWideThreads, a.n_splits, 1, 0);
+    if constexpr (NT == 2 && !kReadOnce) {                         // the variant that may take a second turn
+        if (live_splits > 1 && arrived_last(a.counters + ((size_t)b * st.Hkv + g) * n_cblk + cblk, live_splits))
+            merge_splits<D>(a, b, g, cblk * kWideCols, kWideCols, ncols, group, live_splits, kWideThreads, a.n_splits, 1, 0);
+    } else {
+        if (live_splits <= 1) return;
+        if (!arrived_last(a.counters + ((size_t)b * st.Hkv + g) * n_cblk + cblk, live_splits)) return;
+        merge_splits<D>(a, b, g, cblk * kWideCols, kWideCols, ncols, group, live_splits, kWideThreads, a.n_splits, 1, 0);
+    }
+    }   // turns
 }
 
 template <int D, bool kFp8>
 int launch_bf16(const AttnArgs& args, hipStream_t s)
 {
     AttnArgs a = args;
-    a.col_blocks = 0;
+    a.col_blocks = a.col_paired = 0;
     const int group = a.st.Hq / a.st.Hkv;
     if (a.T_new == 1) {
         dim3 grid(a.st.Hkv, a.B, a.n_splits);
@@ -843,6 +856,13 @@ int launch_bf16(const AttnArgs& args, hipStream_t s)
         dim3 grid(a.st.Hkv, a.B, blocks * a.n_splits);
         if (blocks == 1) {
             hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, true, kFp8>), grid, dim3(512), 0, s, a);
+        } else if (a.n_splits == 1 && blocks >= 4 && blocks % 2 == 0) {
+            // an even number of column blocks: workgroups of two blocks each, all of the same length, the
+            // workgroups of a (sequence, kv head) side by side on one XCD (see the kernel)
+            a.col_blocks = (int)blocks;
+            a.col_paired = 1;
+            const unsigned rounds = ((unsigned)a.B * a.st.Hkv + 7) / 8;
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, false, kFp8>), dim3(8 * rounds * (blocks / 2)), dim3(512), 0, s, a);
         } else if (a.n_splits == 1 && blocks == 2) {
             // two column blocks walk the same pages: side by side on one XCD (see the kernel).  Measured on the
             // Llama-2-13B shape: 512 rows 496 -> 476 us.  With more blocks the side-by-side order costs more at the

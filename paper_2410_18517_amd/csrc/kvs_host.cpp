@@ -553,6 +553,7 @@ static int attention_common(const kvs_store* store, int layer, const void* q, co
     a.n_splits = s.n_splits;
     a.wide_cols = s.wide_cols;
     a.col_blocks = 0;
+    a.col_paired = 0;
     a.adaptive = s.adaptive;
     a.want_splits = s.want_splits;
     a.n_items = s.n_items;

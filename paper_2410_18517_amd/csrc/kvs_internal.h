@@ -42,6 +42,7 @@ struct AttnArgs {
     int32_t wide_cols;      // prefill: 0 = the page-splitting kernel, else columns per workgroup of the shared-page kernel (64, 128, 256)
     int32_t col_blocks;     // set by the launch: > 0 = the shared-page kernel runs on a 1-D grid dealt to the XCDs, with this
                             //   many column blocks per (sequence, kv head); 0 = grid (kv head, sequence, blocks x splits)
+    int32_t col_paired;     //   1 = a workgroup of that grid takes two column blocks in turn, the k-th longest and the k-th shortest
 };
 
 struct CopyArgs {
