@@ -517,11 +517,12 @@ void attn_bf16_wide_kernel(AttnArgs a)
         // 8 k + x, k = 0, 1, ... are consecutive on XCD x.  The workgroups of one (sequence, kv head)
         // take consecutive k: they run side by side on one XCD, walk the same pages at about the same
         // time, and all but the first find a page in that XCD's L2.  Either a workgroup per column
-        // block, or (col_paired, an even number of blocks) a workgroup takes the k-th longest block
-        // and then the k-th shortest, so that all workgroups of the launch do the same amount of work.
+        // block, or (col_paired) a workgroup takes the k-th longest block and then the k-th shortest,
+        // so that the workgroups of the launch do the same amount of work (with an odd number of
+        // blocks the middle one is a workgroup of half that length).
         n_cblk = a.col_blocks;
         split = 0;
-        const int per = a.col_paired ? n_cblk / 2 : n_cblk;        // workgroups per (sequence, kv head)
+        const int per = a.col_paired ? (n_cblk + 1) / 2 : n_cblk;  // workgroups per (sequence, kv head)
         const int xcd = (int)blockIdx.x % 8, k = (int)blockIdx.x / 8;
         const int bg = (k / per) * 8 + xcd;
         if (bg >= a.B * st.Hkv) return;                            // padding of the last round
@@ -529,7 +530,7 @@ void attn_bf16_wide_kernel(AttnArgs a)
         b = bg / st.Hkv;
         cblk_first = n_cblk - 1 - k % per;
         cblk_second = k % per;
-        turns = a.col_paired ? 2 : 1;
+        turns = a.col_paired && cblk_second != cblk_first ? 2 : 1; // (an odd number of blocks: the middle one by itself)
     } else {
         // grid (kv head, sequence, column blocks x context splits), the split index fastest
         g = blockIdx.x;
@@ -856,13 +857,16 @@ int launch_bf16(const AttnArgs& args, hipStream_t s)
         dim3 grid(a.st.Hkv, a.B, blocks * a.n_splits);
         if (blocks == 1) {
             hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, true, kFp8>), grid, dim3(512), 0, s, a);
-        } else if (a.n_splits == 1 && blocks >= 4 && blocks % 2 == 0) {
-            // an even number of column blocks: workgroups of two blocks each, all of the same length, the
-            // workgroups of a (sequence, kv head) side by side on one XCD (see the kernel)
+        } else if (a.n_splits == 1 && blocks >= 4) {
+            // four or more column blocks: workgroups of two blocks each, the k-th longest and the k-th shortest,
+            // so all of the same length (but the middle block of an odd number), the workgroups of a
+            // (sequence, kv head) side by side on one XCD (see the kernel).  Llama-2-13B shape: 1024 rows
+            // 800 -> 740 us, 1280 rows 938 -> 901 us, 2048 rows 1124 -> 1030 us; with three blocks it loses
+            // (768 rows 679 -> 739 us: one workgroup in two is the short middle block), so three keep the grid below.
             a.col_blocks = (int)blocks;
             a.col_paired = 1;
             const unsigned rounds = ((unsigned)a.B * a.st.Hkv + 7) / 8;
-            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, false, kFp8>), dim3(8 * rounds * (blocks / 2)), dim3(512), 0, s, a);
+            hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, false, kFp8>), dim3(8 * rounds * ((blocks + 1) / 2)), dim3(512), 0, s, a);
         } else if (a.n_splits == 1 && blocks == 2) {
             // two column blocks walk the same pages: side by side on one XCD (see the kernel).  Measured on the
             // Llama-2-13B shape: 512 rows 496 -> 476 us.  With more blocks the side-by-side order costs more at the

@@ -346,6 +346,30 @@ def test_shared_page_prefill_kernels(kb, d, Hq, Hkv, B, T_new):
         assert rel_l2_rows(short[b:b + 1], want[:, -tail:]).max() <= REL_L2_ATTENTION, b
 
 
+# Four or more 256-column blocks per (sequence, kv head): a workgroup takes the k-th longest and then
+# the k-th shortest block (an odd number leaves the middle block to a workgroup of its own), three
+# blocks keep one workgroup per block.  Ragged last block, a group size of two, different starts.
+@pytest.mark.parametrize("Hq,Hkv,B,T_new", [(8, 8, 8, 800),        # 4 blocks, the last one with 32 columns
+                                            (8, 8, 8, 1100),       # 5 blocks: two pairs and the middle block
+                                            (16, 8, 6, 850),       # group 2: 1700 columns, 7 blocks
+                                            (8, 8, 16, 700)])      # 3 blocks: one workgroup each
+def test_prefill_many_column_blocks(kb, Hq, Hkv, B, T_new):
+    d, L = 128, 2
+    cap = T_new + 120
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, "bf16", cap, share, paged=True, seed=53)
+    rng = np.random.default_rng(53)
+    start = rng.integers(0, cap - T_new + 1, size=B).astype(np.int32)
+    start[0], start[-1] = 0, cap - T_new
+    q = case.q(1, rows=T_new)
+    got = kb.kvs_prefill_attention(case.store, 1, q.cuda(), start).cpu().numpy()
+    assert np.isfinite(got).all()
+    for b in (0, B // 2, B - 1):
+        want = orc.shared_attention(1, share, [case.K[0][b:b + 1], None], [case.V[0][b:b + 1], None],
+                                    inputs.to_oracle_array(q[b:b + 1]), start[b:b + 1])
+        assert rel_l2_rows(got[b:b + 1], want).max() <= REL_L2_ATTENTION, b
+
+
 # Few (sequence, kv head) pairs: the shared-page kernels split the context over workgroups too, and
 # the last workgroup of a column block to arrive merges the states.  By the host's own choice at a
 # long context, and with a forced split of 4 or 8 pages at a short one; start positions that leave
