@@ -518,8 +518,7 @@ void attn_bf16_wide_kernel(AttnArgs a)
         // take consecutive k: they run side by side on one XCD, walk the same pages at about the same
         // time, and all but the first find a page in that XCD's L2.  Either a workgroup per column
         // block, or (col_paired) a workgroup takes the k-th longest block and then the k-th shortest,
-        // so that the workgroups of the launch do the same amount of work (with an odd number of
-        // blocks the middle one is a workgroup of half that length).
+        // so that the workgroups of the launch do the same amount of work.
         n_cblk = a.col_blocks;
         split = 0;
         const int per = a.col_paired ? (n_cblk + 1) / 2 : n_cblk;  // workgroups per (sequence, kv head)
@@ -528,9 +527,13 @@ void attn_bf16_wide_kernel(AttnArgs a)
         if (bg >= a.B * st.Hkv) return;                            // padding of the last round
         g = bg % st.Hkv;
         b = bg / st.Hkv;
-        cblk_first = n_cblk - 1 - k % per;
-        cblk_second = k % per;
-        turns = a.col_paired && cblk_second != cblk_first ? 2 : 1; // (an odd number of blocks: the middle one by itself)
+        // block i of a prompt walks about i + 1 times the pairs of block 0: an even number of blocks pairs
+        // i with n - 1 - i; an odd number leaves the longest block by itself and pairs the others so that
+        // every pair is as long as it (exactly so when the chunk starts the sequence)
+        const int which = k % per, odd = n_cblk & 1;
+        cblk_first = n_cblk - 1 - which;
+        cblk_second = which - odd;
+        turns = a.col_paired && cblk_second >= 0 ? 2 : 1;
     } else {
         // grid (kv head, sequence, column blocks x context splits), the split index fastest
         g = blockIdx.x;
@@ -858,11 +861,11 @@ int launch_bf16(const AttnArgs& args, hipStream_t s)
         if (blocks == 1) {
             hipLaunchKernelGGL((attn_bf16_wide_kernel<D, 2, 8, true, kFp8>), grid, dim3(512), 0, s, a);
         } else if (a.n_splits == 1 && blocks >= 4) {
-            // four or more column blocks: workgroups of two blocks each, the k-th longest and the k-th shortest,
-            // so all of the same length (but the middle block of an odd number), the workgroups of a
-            // (sequence, kv head) side by side on one XCD (see the kernel).  Llama-2-13B shape: 1024 rows
-            // 800 -> 740 us, 1280 rows 938 -> 901 us, 2048 rows 1124 -> 1030 us; with three blocks it loses
-            // (768 rows 679 -> 739 us: one workgroup in two is the short middle block), so three keep the grid below.
+            // four or more column blocks: workgroups of two blocks each, a long one and a short one, all
+            // about the same length, the workgroups of a (sequence, kv head) side by side on one XCD (see
+            // the kernel).  Llama-2-13B shape, the last rows of a 2048-token context: 1024 rows 800 -> 740 us,
+            // 1280 rows 938 -> 878 us, 1792 rows 1088 -> 1014 us, all 2048 rows 1124 -> 1030 us; three blocks
+            // lose (768 rows 679 -> 705 us) and keep the grid below.
             a.col_blocks = (int)blocks;
             a.col_paired = 1;
             const unsigned rounds = ((unsigned)a.B * a.st.Hkv + 7) / 8;
