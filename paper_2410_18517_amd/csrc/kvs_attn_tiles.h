@@ -169,21 +169,39 @@ __device__ __forceinline__ void merge_splits(const AttnArgs& a, int b, int g, in
         const size_t row = ((size_t)b * a.T_new + r) * st.Hq + g * group + hc;
         const float* part = a.partials + (row * rec_per_row + rec_first) * (size_t)(D + 2);
         const size_t step = (size_t)rec_per_split * (D + 2);
+        // Eight records at a time, all their loads issued before any is used: one memory round trip
+        // per eight parts (a pass for the maximum and a pass for the sums were two to three per
+        // eight).  Beyond eight parts the running reference moves as in the online softmax.
+        constexpr int kAtOnce = 8;
         float M = -INFINITY;
-#pragma unroll 8
-        for (int s = 0; s < live_splits; ++s) M = fmaxf(M, fetch_pair(part + s * step + D)[0]);
-        const float M_use = M == -INFINITY ? 0.f : M;
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
         float lt = 0.f;
-#pragma unroll 4
-        for (int s = 0; s < live_splits; ++s) {
-            const float* ps = part + s * step;
-            const floatx2 ml = fetch_pair(ps + D);
-            const floatx2 lo = fetch_pair(ps + d4);
-            const floatx2 hi = fetch_pair(ps + d4 + 2);
-            const float wgt = __builtin_amdgcn_exp2f(ml[0] - M_use);   // empty splits carry m = -inf
-            acc += wgt * floatx4{lo[0], lo[1], hi[0], hi[1]};
-            lt += wgt * ml[1];
+        for (int s0 = 0; s0 < live_splits; s0 += kAtOnce) {
+            floatx2 ml[kAtOnce], lo[kAtOnce], hi[kAtOnce];
+#pragma unroll
+            for (int u = 0; u < kAtOnce; ++u) {
+                const float* ps = part + (size_t)(s0 + u < live_splits ? s0 + u : s0) * step;   // past the end: a record that exists
+                ml[u] = fetch_pair(ps + D);
+                lo[u] = fetch_pair(ps + d4);
+                hi[u] = fetch_pair(ps + d4 + 2);
+            }
+            float Mc = M;
+#pragma unroll
+            for (int u = 0; u < kAtOnce; ++u) {
+                if (s0 + u >= live_splits) ml[u][0] = -INFINITY;     // weight 0
+                Mc = fmaxf(Mc, ml[u][0]);
+            }
+            const float M_use = Mc == -INFINITY ? 0.f : Mc;
+            const float keep = __builtin_amdgcn_exp2f(M - M_use);    // 0 while nothing has been added (M = -inf)
+            acc *= keep;
+            lt *= keep;
+#pragma unroll
+            for (int u = 0; u < kAtOnce; ++u) {
+                const float wgt = __builtin_amdgcn_exp2f(ml[u][0] - M_use);   // empty parts carry m = -inf
+                acc += wgt * floatx4{lo[u][0], lo[u][1], hi[u][0], hi[u][1]};
+                lt += wgt * ml[u][1];
+            }
+            M = Mc;
         }
         const float inv = lt > 0.f ? 1.f / lt : 0.f;
         *reinterpret_cast<floatx4*>(a.out + row * D + d4) = acc * inv;
