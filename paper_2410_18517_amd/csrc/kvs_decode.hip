@@ -12,8 +12,8 @@
 // ones, or a store far below its capacity therefore keeps every compute unit streaming the same
 // number of bytes.
 //
-// A workgroup walks its share octet by octet (eight pages, a pair per wavefront; two octets are in
-// flight per wavefront) and keeps one online-softmax state per wavefront, as the split kernel in
+// A workgroup walks its share octet by octet (eight pages, a pair per wavefront; 16 KiB are in
+// flight per wavefront, one to four octets by page size) and keeps one online-softmax state per wavefront, as the split kernel in
 // kvs_attention.hip does.  Where the line passes from one segment to the next, the four states are
 // merged through LDS and the segment is finished: written out normalised when the whole segment
 // lay inside this share, else published as a partial state.  A workgroup publishes at most two
