@@ -33,6 +33,7 @@ namespace {
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
+constexpr int kLargeLaunchOctets = 24;     // octets per launched workgroup from which a launch counts as large
 static_assert(kOctetPages == 2 * kWaves, "an octet is one pair of pages per wavefront");
 
 // A page through a buffer descriptor of `bytes` bytes (the page's size, or 0 for a page that does
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int quad = lane >> 4, col = lane & 15;
-    const int wg = blockIdx.x, n_wg = gridDim.x;
+    const int wg = blockIdx.x, n_launched = gridDim.x;
     const int B = a.B, Hkv = st.Hkv, group = st.Hq / st.Hkv;
     const int max_pages = st.max_blocks_per_seq;
     const int cap = max_pages * kPageTokens;
@@ -87,7 +88,22 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
     // full, and the page-table entries of this wavefront's first two pairs are fetched on that
     // guess in the same round trip as the lengths (right exactly when the store is full).
     const int full_octs = (max_pages + kOctetPages - 1) / kOctetPages;
-    const FlatShare guess = flat_share(wg, n_wg, Hkv * B * full_octs);
+    // How many of the launched workgroups stream.  A large launch over bf16 pages of 128 channels
+    // takes three quarters of them: one workgroup per compute unit asks for more than the memory
+    // delivers, the XCDs are then served unequally (their workgroups finish up to 10 us apart on
+    // 4 x 32k tokens) and the launch waits for the slowest; with 24 instead of 32 workgroups per XCD
+    // all of them stream at the same rate (4 x 32k tokens 84.5 -> 83.1 us, 32 ragged sequences 98.0 ->
+    // 95.6 us).  Not where the shares are whole segments (nothing is published or merged then, which
+    // is worth more: 8 x 4096 tokens, 32 kv heads 82.7 against 83.5 us), not for small launches
+    // (4 x 16k tokens 45.3 against 45.8 us) and not for fp8 pages, whose widening needs every compute unit.
+    auto streaming_workgroups = [&](int total_octs, int seg_octs) {    // seg_octs: every segment's length, 0 if they differ
+        if (kFp8 || D != 128 || n_launched < 64 || total_octs < kLargeLaunchOctets * n_launched) return n_launched;
+        if (seg_octs > 0 && total_octs % n_launched == 0 && (total_octs / n_launched) % seg_octs == 0) return n_launched;
+        const int n = (n_launched - n_launched / 4) & ~7;
+        return n >= Hkv ? n : n_launched;
+    };
+    const int n_guess = streaming_workgroups(Hkv * B * full_octs, full_octs);
+    const FlatShare guess = wg < n_guess ? flat_share(wg, n_guess, Hkv * B * full_octs) : FlatShare{0, 0};
     int guess_b[2], guess_page[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -134,8 +150,10 @@ __global__ __launch_bounds__(kThreads) void attn_decode_flat_kernel(AttnArgs a)
     }
     const int head_octs = __builtin_amdgcn_readlane(incl, 63);       // octets of one kv head
     const int total = head_octs * Hkv;
+    const int octs_first = __builtin_amdgcn_readfirstlane(octs_lane);
+    const int n_wg = streaming_workgroups(total, __all(lane >= B || octs_lane == octs_first) ? octs_first : 0);
     const FlatPlan plan(n_wg, total);
-    const FlatShare mine = plan.share(wg);
+    const FlatShare mine = wg < n_wg ? plan.share(wg) : FlatShare{0, 0};
 
     auto advance = [&](Cursor& c) {                                  // only called while an octet follows on the line
         if (++c.oi < c.octs) return;

@@ -116,3 +116,44 @@ def test_other_grid_sizes(kb, dtype, n_wg):
         _decode_and_check(kb, case, 0, lens[::-1].copy())
     finally:
         assert kb.lib().kvs_testing_set_decode_workgroups(0) == kb.KVS_OK
+
+
+def test_large_launches_stream_on_three_quarters_of_the_grid(kb):
+    """From 24 octets per launched workgroup on, a launch over bf16 pages of 128 channels shares its
+    line among three quarters of the workgroups and the rest leave at once (the memory system serves
+    fewer streams more evenly): with 64 launched the result is, bit for bit, that of 48, for equal and
+    for ragged lengths and for a step that carries its own token; a launch whose shares are whole
+    segments keeps all its workgroups."""
+    Hq, Hkv, d = 8, 2, 128
+    share = np.array([0, 0], np.int32)
+    ragged = np.array([16384, 10001, 12800, 15000, 11111, 16000, 13000, 14567], np.int32)
+    assert sum((int(n) + 127) // 128 for n in ragged) * Hkv >= 24 * 64
+    case = Case(kb, 2, Hq, Hkv, d, 8, "bf16", 16384, share, paged=True, seed=113)
+    q = case.q(1)
+    outs = {}
+    try:
+        for n_wg in (64, 48):
+            assert kb.lib().kvs_testing_set_decode_workgroups(n_wg) == kb.KVS_OK
+            for name, lens in (("equal", np.full(8, 12288, np.int32)), ("ragged", ragged)):
+                outs[name, n_wg] = kb.kvs_decode_attention(case.store, 1, q.cuda(), lens).cpu().numpy()
+                if n_wg == 64:
+                    want = orc.decode_attention(1, share, case.K, case.V, inputs.to_oracle_array(q), lens)
+                    assert rel_l2_rows(outs[name, n_wg], want).max() <= REL_L2_ATTENTION
+        for name in ("equal", "ragged"):
+            assert np.array_equal(outs[name, 64], outs[name, 48]), name
+        # whole segments per share: 64 (sequence, kv head) segments of 24 octets on 64 workgroups
+        assert kb.lib().kvs_testing_set_decode_workgroups(64) == kb.KVS_OK
+        whole = Case(kb, 2, 8, 8, d, 8, "bf16", 3072, share, paged=True, seed=127)
+        _decode_and_check(kb, whole, 1, np.full(8, 3072, np.int32))
+        # a step with its own token on the large ragged launch
+        k_new = inputs.normal((8, 1, Hkv, d), 113, 700)
+        v_new = inputs.normal((8, 1, Hkv, d), 113, 701)
+        K, V = [case.K[0].copy(), None], [case.V[0].copy(), None]
+        for b in range(8):
+            K[0][b, ragged[b] - 1] = inputs.to_oracle_array(k_new)[b, 0]
+            V[0][b, ragged[b] - 1] = inputs.to_oracle_array(v_new)[b, 0]
+        got = kb.kvs_decode_step(case.store, 0, q.cuda(), k_new.cuda(), v_new.cuda(), ragged).cpu().numpy()
+        want = orc.decode_attention(0, share, K, V, inputs.to_oracle_array(q), ragged)
+        assert rel_l2_rows(got, want).max() <= REL_L2_ATTENTION
+    finally:
+        assert kb.lib().kvs_testing_set_decode_workgroups(0) == kb.KVS_OK
