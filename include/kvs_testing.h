@@ -22,10 +22,13 @@ extern "C" {
 int kvs_testing_force_split_tokens(int tokens);
 
 /*
- * Workgroups of a decode launch that shares its pages out by tokens (0: the built-in choice, one
- * per compute unit; never fewer than the store has kv heads).  With a handful of workgroups every
- * share holds many sequences, and one with thousands the shares are single octets, which a test
- * cannot arrange otherwise.  Process-wide; query the workspace size again after changing it.
+ * Workgroups launched for a decode call that shares its pages out by tokens (0: the built-in
+ * choice, one per compute unit; never fewer than the store has kv heads).  With a handful of
+ * workgroups every share holds many sequences, and with thousands the shares are single octets,
+ * which a test cannot arrange otherwise.  From 64 launched workgroups on, a launch over bf16 pages
+ * of 128 channels with at least 24 octets per launched workgroup, whose shares are not whole
+ * segments, lets only three quarters of them (a multiple of eight) take a share.  Process-wide;
+ * query the workspace size again after changing it.
  */
 int kvs_testing_set_decode_workgroups(int n);
 
