@@ -276,7 +276,7 @@ int kvs_prefill_attention(const kvs_store* store, int layer, const void* q,
  * set); counts are clamped to [0, max_keep].  Positions at and after the count keep stale data.
  *   keep_idx device int32 [B][Hkv][max_keep];  keep_count device int32 [B][Hkv].
  * Returns KVS_NOOP for a layer that reads a donor's cache (the donor's compaction is the one
- * it sees).  Cost: the workgroups of a (sequence, kv head) walk its kept tokens in order, 128
+ * it sees).  Cost: the workgroups of a (sequence, kv head) walk its kept tokens in order, 1024
  * at a time; a maintenance operation, not part of the decode step.
  */
 int kvs_compact_kv(const kvs_store* store, int layer, const int32_t* keep_idx,
