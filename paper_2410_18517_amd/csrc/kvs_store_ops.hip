@@ -4,6 +4,8 @@
 // gets here for writes: the host returns before any launch.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kvs_device.h"
 #include "kvs_internal.h"
 
@@ -105,14 +107,18 @@ __global__ void copy_rows_kernel(CopyArgs a)
     }
 }
 
-// Append of several rows per sequence to a bf16 store (prefill chunks, store fills): one
+// Append of several rows per sequence to a bf16 or fp8 store (prefill chunks, store fills): one
 // workgroup per (sequence, kv head, page touched).  K rows go straight to their operand-order
-// position, 16 bytes per thread.  V rows are staged in LDS and leave as whole 16-byte operand
-// chunks (four tokens x two channels) wherever all four tokens of the chunk are being written;
-// the ragged first and last tokens of the append fall back to 2-byte stores.  A whole-page
-// append therefore writes each page as 4 KiB of full-width stores instead of 2-byte scatters.
-__global__ __launch_bounds__(256) void append_pages_bf16_kernel(CopyArgs a)
+// position, one 16-byte (fp8: 8-byte) piece per thread.  V rows are staged in LDS and leave as whole
+// 16-byte operand chunks (bf16: four tokens x two channels; fp8: four tokens x four channels)
+// wherever all four tokens of the chunk are being written; the ragged first and last tokens of the
+// append fall back to single elements.  A whole-page append therefore writes each page in full-width
+// stores instead of 2-byte (1-byte) scatters.  fp8: the rows are rounded to E4M3 by the integer
+// routine every other writer of that store uses.
+template <bool kFp8>
+__global__ __launch_bounds__(256) void append_pages_kernel(CopyArgs a)
 {
+    using Elem = std::conditional_t<kFp8, unsigned char, unsigned short>;
     const StoreView& st = a.st;
     const int D = st.head_dim;                    // 64 or 128
     const int g = blockIdx.y, b = blockIdx.z;
@@ -127,38 +133,76 @@ __global__ __launch_bounds__(256) void append_pages_bf16_kernel(CopyArgs a)
     const int t_hi = (int)(end - tok0 < kPageTokens ? end - tok0 : kPageTokens);
     const int blk = block_of(st, b, (int)page);
     if (blk < 0 || blk >= st.num_blocks) return;
-    unsigned short* kp = static_cast<unsigned short*>(st.pool) + page_offset(st, resolve_slot(st), blk, g);
-    unsigned short* vp = kp + kPageTokens * D;
-    __shared__ unsigned short vs[kPageTokens][128 + 8];
+    Elem* kp = static_cast<Elem*>(st.pool) + page_offset(st, resolve_slot(st), blk, g);
+    Elem* vp = kp + kPageTokens * D;
+    __shared__ Elem vs[kPageTokens][128 + 8];
 
-    const int chunks = D / 8;                     // 16-byte chunks per row
+    const int chunks = D / 8;                     // 8-channel pieces per row
     const int t = threadIdx.x / 16, ch = threadIdx.x % 16;
     if (t >= t_lo && t < t_hi && ch < chunks) {
         const size_t row = (((size_t)b * a.T + (size_t)(tok0 + t - start)) * st.Hkv + g) * D + (size_t)ch * 8;
-        *reinterpret_cast<uint4*>(kp + k_index_bf16(t, ch * 8)) =
-            *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(a.k) + row);
-        *reinterpret_cast<uint4*>(&vs[t][ch * 8]) =
-            *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(a.v) + row);
+        const uint4 kk = *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(a.k) + row);
+        const uint4 vv = *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(a.v) + row);
+        if constexpr (kFp8) {
+            const unsigned kw[4] = {kk.x, kk.y, kk.z, kk.w}, vw[4] = {vv.x, vv.y, vv.z, vv.w};
+            unsigned k8[2] = {0, 0}, v8[2] = {0, 0};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                k8[e >> 2] |= bf16_to_e4m3((kw[e >> 1] >> ((e & 1) * 16)) & 0xffffu) << (8 * (e & 3));
+                v8[e >> 2] |= bf16_to_e4m3((vw[e >> 1] >> ((e & 1) * 16)) & 0xffffu) << (8 * (e & 3));
+            }
+            *reinterpret_cast<uint2*>(kp + k_index_fp8(t, ch * 8)) = make_uint2(k8[0], k8[1]);
+            *reinterpret_cast<uint2*>(&vs[t][ch * 8]) = make_uint2(v8[0], v8[1]);
+        } else {
+            *reinterpret_cast<uint4*>(kp + k_index_bf16(t, ch * 8)) = kk;
+            *reinterpret_cast<uint4*>(&vs[t][ch * 8]) = vv;
+        }
     }
     __syncthreads();
-    // output chunk o: channels (o/64)*32 + {0,16} + o%16, tokens 4*((o/16)%4) .. +3
-    for (int o = threadIdx.x; o < D * 2; o += 256) {
-        const int cp = o / 64, quad = (o / 16) % 4, dl = o % 16;
-        unsigned short e[8];
+    if constexpr (kFp8) {
+        // output chunk o: channels (o/64)*64 + {0,16,32,48} + o%16, tokens 4*((o/16)%4) .. +3
+        for (int o = threadIdx.x; o < D; o += 256) {
+            const int cp = o / 64, quad = (o / 16) % 4, dl = o % 16;
+            unsigned char e[16];
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) e[j * 4 + i] = vs[quad * 4 + i][cp * 32 + j * 16 + dl];
-        unsigned short* dst = vp + (size_t)o * 8;
-        if (quad * 4 >= t_lo && quad * 4 + 4 <= t_hi) {
-            *reinterpret_cast<uint4*>(dst) = make_uint4(e[0] | (unsigned)e[1] << 16, e[2] | (unsigned)e[3] << 16,
-                                                        e[4] | (unsigned)e[5] << 16, e[6] | (unsigned)e[7] << 16);
-        } else {
+                for (int i = 0; i < 4; ++i) e[j * 4 + i] = vs[quad * 4 + i][cp * 64 + j * 16 + dl];
+            unsigned char* dst = vp + (size_t)o * 16;
+            if (quad * 4 >= t_lo && quad * 4 + 4 <= t_hi) {
+                unsigned w[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    w[j] = e[j * 4] | (unsigned)e[j * 4 + 1] << 8 | (unsigned)e[j * 4 + 2] << 16 | (unsigned)e[j * 4 + 3] << 24;
+                *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (quad * 4 + i >= t_lo && quad * 4 + i < t_hi) dst[j * 4 + i] = e[j * 4 + i];
+            }
+        }
+    } else {
+        // output chunk o: channels (o/64)*32 + {0,16} + o%16, tokens 4*((o/16)%4) .. +3
+        for (int o = threadIdx.x; o < D * 2; o += 256) {
+            const int cp = o / 64, quad = (o / 16) % 4, dl = o % 16;
+            unsigned short e[8];
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (quad * 4 + i >= t_lo && quad * 4 + i < t_hi) dst[j * 4 + i] = e[j * 4 + i];
+                for (int i = 0; i < 4; ++i) e[j * 4 + i] = vs[quad * 4 + i][cp * 32 + j * 16 + dl];
+            unsigned short* dst = vp + (size_t)o * 8;
+            if (quad * 4 >= t_lo && quad * 4 + 4 <= t_hi) {
+                *reinterpret_cast<uint4*>(dst) = make_uint4(e[0] | (unsigned)e[1] << 16, e[2] | (unsigned)e[3] << 16,
+                                                            e[4] | (unsigned)e[5] << 16, e[6] | (unsigned)e[7] << 16);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (quad * 4 + i >= t_lo && quad * 4 + i < t_hi) dst[j * 4 + i] = e[j * 4 + i];
+            }
         }
     }
 }
@@ -302,11 +346,11 @@ int launch_check_store(const CheckArgs& a, void* stream)
 
 int launch_append(const CopyArgs& a, void* stream)
 {
-    if (a.st.dtype == 1 && a.T >= 4) {
+    if (a.st.dtype != 0 && a.T >= 4) {
         // pages a sequence's rows can touch: T rows starting anywhere inside a page
-        const unsigned pages = (unsigned)((a.T + kPageTokens - 1) / kPageTokens + 1);
-        hipLaunchKernelGGL(append_pages_bf16_kernel, dim3(pages, a.st.Hkv, a.B), dim3(256), 0,
-                           static_cast<hipStream_t>(stream), a);
+        const dim3 grid((unsigned)((a.T + kPageTokens - 1) / kPageTokens + 1), a.st.Hkv, a.B);
+        if (a.st.dtype == 1) hipLaunchKernelGGL(append_pages_kernel<false>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+        else hipLaunchKernelGGL(append_pages_kernel<true>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
         return (int)hipGetLastError();
     }
     const int per = a.st.dtype == 0 ? 4 : 8;

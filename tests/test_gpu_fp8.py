@@ -127,3 +127,37 @@ def test_shared_page_prefill_over_fp8_slots(kb, d, Hq, Hkv, B, T_new):
                                 inputs.to_oracle_array(q[b:b + 1, -tail:].contiguous()), start[b:b + 1] + (T_new - tail))
     assert rel_l2_rows(short[b:b + 1], want).max() <= REL_L2_ATTENTION
     assert rel_l2_rows(short, got[:, -tail:].astype(np.float64)).max() <= 2 * REL_L2_ATTENTION
+
+
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("paged", [True, False])
+def test_chunk_appends_at_ragged_positions_store_the_oracle_codes(kb, d, paged):
+    """Several rows at once into an fp8 store, starting and ending inside pages (the page-wise append
+    writes whole 16-byte pieces where all four tokens of a piece are new and single bytes elsewhere):
+    what was written reads back as the oracle rounds it, what was there before is untouched, and the
+    one-row append of a decode step lands in the same places."""
+    L, Hq, Hkv, B, cap, T0, T = 2, 4, 2, 3, 96, 37, 20
+    share = np.array([0, 0], np.int32)
+    case = Case(kb, L, Hq, Hkv, d, B, "fp8", cap, share, paged=paged, seed=41, fill_tokens=T0)
+    start = np.array([37, 5, 62], np.int32)                  # continues, overwrites the middle, leaves a gap
+    k_new = inputs.normal((B, T, Hkv, d), 41, 500)
+    v_new = inputs.normal((B, T, Hkv, d), 41, 501)
+    assert kb.kvs_append_kv(case.store, 0, k_new.cuda(), v_new.cuda(), start) == kb.KVS_OK
+    Ko = np.zeros((B, cap, Hkv, d), np.uint16); Vo = np.zeros((B, cap, Hkv, d), np.uint16)
+    Ko[:, :T0], Vo[:, :T0] = case.K[0], case.V[0]
+    for b in range(B):
+        Ko[b, start[b]:start[b] + T] = stored_fp8(inputs.to_oracle_array(k_new))[b]
+        Vo[b, start[b]:start[b] + T] = stored_fp8(inputs.to_oracle_array(v_new))[b]
+    one_k = inputs.normal((B, 1, Hkv, d), 41, 502)
+    one_v = inputs.normal((B, 1, Hkv, d), 41, 503)
+    at = start + T                                            # one more row behind each chunk
+    assert kb.kvs_append_kv(case.store, 0, one_k.cuda(), one_v.cuda(), at) == kb.KVS_OK
+    for b in range(B):
+        Ko[b, at[b]] = stored_fp8(inputs.to_oracle_array(one_k))[b, 0]
+        Vo[b, at[b]] = stored_fp8(inputs.to_oracle_array(one_v))[b, 0]
+    for layer in (0, 1):                                      # the recipient reads the same slot
+        k, v = kb.kvs_gather_kv(case.store, layer, 0, cap, B)
+        k, v = inputs.to_oracle_array(k), inputs.to_oracle_array(v)
+        for b in range(B):
+            for lo, hi in ((0, T0), (start[b], start[b] + T + 1)):
+                assert np.array_equal(k[b, lo:hi], Ko[b, lo:hi]) and np.array_equal(v[b, lo:hi], Vo[b, lo:hi]), (layer, b, lo)
