@@ -107,6 +107,7 @@ def bench_prefill(args, torch, kb, inputs, dev):
         kb.kvs_append_kv(store, l, k, v, zeros)
     q = torch.randn((w.B, T, w.Hq, w.d), device=dev, generator=gen).bfloat16()
     k_new = torch.randn((w.B, T, w.Hkv, w.d), device=dev, generator=gen).bfloat16()
+    v_new = torch.randn((w.B, T, w.Hkv, w.d), device=dev, generator=gen).bfloat16()
     start = torch.full((w.B,), w.context - T, dtype=torch.int32, device=dev)
     out = torch.empty((w.B, T, w.Hq, w.d), dtype=torch.float32, device=dev)
     ws = store.workspace(w.B, T)
@@ -117,7 +118,7 @@ def bench_prefill(args, torch, kb, inputs, dev):
         it[0] += 1
 
     def append():
-        kb.kvs_append_kv(store, it[0] % n_layers, k_new, k_new, start)
+        kb.kvs_append_kv(store, it[0] % n_layers, k_new, v_new, start)
         it[0] += 1
 
     if args.traffic_probe:
@@ -156,6 +157,7 @@ def bench_prefill(args, torch, kb, inputs, dev):
         "config": {"workload": "llama2-13b prefill chunk" + (", fp8 slots" if store_dtype == "fp8" else ""), "batch": w.B, "rows": T, "prefix": w.context - T,
                    "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d},
         "append_us": round(append_us, 2),
+        "append_bytes": w.B * T * w.Hkv * w.d * 2 * (2 + (1 if store_dtype == "fp8" else 2)),   # rows read + pages written
         "roofline": roof}))
 
 
